@@ -1,0 +1,324 @@
+/*
+ * CPU oracle for one batched Leader-SGD step.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain statement of what the method computes, written
+ * from the paper (arXiv 1905.10395).  It is used by the tests, by the smoke
+ * check and by the CPU-baseline leg of the benchmark, and by nothing else.
+ * It shares no code, header, table or helper with the HIP library.
+ *
+ * Conventions
+ *   - State (x, m, Z, g, losses) is stored in fp32, the same bytes the GPU
+ *     holds.  Every sum, dot product and update expression is evaluated in
+ *     fp64 and rounded once to fp32 where it is stored.
+ *   - Workers are rows of x[W, ld]; group j owns rows [off[j], off[j+1]).
+ *   - Z[(G+1), ld] holds the leader copies kept between communications
+ *     (Algorithm 1 "Set x~^j, x~"; supplement B.1, communication periods):
+ *     rows 0..G-1 local leaders, row G the global leader.
+ *
+ * Pins (tests/test_oracle_*.py): zero pull coefficients reduce to SGD; the
+ * leader's own pull vanishes; the affine form X+ = (1-eta*lam)X + eta*lam*Z -
+ * eta*grad of the matrix-completion supplement; several leaders collapse to
+ * one (Section 3, first paragraph); fixed-leader limit on a diagonal
+ * quadratic and the bound of Theorem 2; monotone leader value (Lemma
+ * "leader_descent"); the sinc example's optimum -0.2172 (supplement Table 1);
+ * grad F = (XX^T - M)X for the dense PSD problem; finite differences;
+ * brute-force argmin.
+ *
+ * Parity unpinned by the paper (fixed by declaration): where momentum enters
+ * (heavy ball on the full direction by default), the bf16 rounding points of
+ * the MLP workload, the loss normalisation c of the matrix-completion batch.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_NESTEROV            1
+#define ORACLE_LEADER_EXEMPT       2
+#define ORACLE_PULL_UNSCALED       4
+#define ORACLE_MOMENTUM_GRAD_ONLY  8
+
+/* ------------------------------------------------------------------ */
+/* Leader selection: Eq. 1/2 argmin definitions; Algorithm 1 "Determine
+ * the local best workers / the global best worker".  Ties go to the lowest
+ * index; NaN counts as +infinity.                                      */
+/* ------------------------------------------------------------------ */
+static double sel_value(float v) { return isnan(v) ? INFINITY : (double)v; }
+
+static void argmin_range(const float* losses, int lo, int hi, int32_t* idx, double* gap)
+{
+    int best = lo;
+    double bv = sel_value(losses[lo]);
+    for (int i = lo + 1; i < hi; ++i) {
+        double v = sel_value(losses[i]);
+        if (v < bv) { bv = v; best = i; }
+    }
+    *idx = best;
+    if (gap) {
+        double second = INFINITY;
+        for (int i = lo; i < hi; ++i)
+            if (i != best) { double v = sel_value(losses[i]); if (v < second) second = v; }
+        if (isinf(second) && isinf(bv)) *gap = 0.0;            /* all-infinite group: a tie */
+        else if (isinf(second)) *gap = INFINITY;               /* single finite member      */
+        else { double den = fabs(bv) > 1e-30 ? fabs(bv) : 1e-30; *gap = (second - bv) / den; }
+    }
+}
+
+/* lead[G], glead[1] are updated only for refreshed groups / a global refresh.
+ * gaps (optional, [G+1]) receives (second best - best)/|best| per refreshed
+ * selection, used by tests to detect legitimate near-ties.             */
+void lsgd_oracle_select_leaders(const float* losses, int W, int G, const int32_t* off,
+                                const uint8_t* refresh_local, int refresh_global,
+                                int32_t* lead, int32_t* glead, double* gaps)
+{
+    for (int j = 0; j < G; ++j) {
+        if (refresh_local && !refresh_local[j]) continue;
+        argmin_range(losses, off[j], off[j + 1], &lead[j], gaps ? &gaps[j] : 0);
+    }
+    if (refresh_global) argmin_range(losses, 0, W, glead, gaps ? &gaps[G] : 0);
+}
+
+/* ------------------------------------------------------------------ */
+/* Pull update.  Supplement B.1: x+ = x - eta*(g + lam*(x - z)); with two
+ * leaders (Eq. 2 / Eq. 3) the pulls add.  Leader copies are taken from
+ * the pre-update parameters at a refresh, kept otherwise.              */
+/* ------------------------------------------------------------------ */
+void lsgd_oracle_pull_update(float* x, float* m, const float* g, float* Z,
+                             int W, int64_t P, int64_t ld, int G, const int32_t* off,
+                             const int32_t* lead, int32_t glead,
+                             const uint8_t* refresh_local, int refresh_global,
+                             float eta_f, float lamL_f, float lamG_f, float mu_f,
+                             int flags, float wd_f)
+{
+    const double eta = eta_f, mu = mu_f, wd = wd_f;
+    double lamL = lamL_f, lamG = lamG_f;
+    if (flags & ORACLE_PULL_UNSCALED) { lamL = lamL / eta; lamG = lamG / eta; } /* Eq. 3 as printed */
+
+    /* step 2: copy the selected leaders' current parameters */
+    for (int j = 0; j < G; ++j)
+        if (lamL_f != 0.0f && (!refresh_local || refresh_local[j]))
+            memcpy(Z + (int64_t)j * ld, x + (int64_t)lead[j] * ld, sizeof(float) * (size_t)P);
+    if (lamG_f != 0.0f && refresh_global)
+        memcpy(Z + (int64_t)G * ld, x + (int64_t)glead * ld, sizeof(float) * (size_t)P);
+
+    /* step 3: every worker moves, all from pre-update values (Z holds the leaders') */
+    #pragma omp parallel for schedule(static)
+    for (int i = 0; i < W; ++i) {
+        int j = 0;
+        while (!(off[j] <= i && i < off[j + 1])) ++j;
+        double cL = lamL, cG = lamG;
+        if (flags & ORACLE_LEADER_EXEMPT) {
+            if (i == lead[j]) cL = 0.0;
+            if (i == glead) cG = 0.0;
+        }
+        const float* zL = Z + (int64_t)j * ld;
+        const float* zG = Z + (int64_t)G * ld;
+        float* xi = x + (int64_t)i * ld;
+        float* mi = m ? m + (int64_t)i * ld : 0;
+        const float* gi = g + (int64_t)i * ld;
+        for (int64_t p = 0; p < P; ++p) {
+            double xv = xi[p];
+            double gv = gi[p];
+            if (wd_f != 0.0f) gv += wd * xv;
+            double pull = 0.0;
+            if (lamL_f != 0.0f) pull += cL * (xv - (double)zL[p]);
+            if (lamG_f != 0.0f) pull += cG * (xv - (double)zG[p]);
+            double step;
+            if (mu_f == 0.0f) {
+                step = gv + pull;
+            } else if (flags & ORACLE_MOMENTUM_GRAD_ONLY) {
+                double mv = mu * (double)mi[p] + gv;
+                mi[p] = (float)mv;
+                mv = (double)mi[p];
+                step = ((flags & ORACLE_NESTEROV) ? gv + mu * mv : mv) + pull;
+            } else {
+                double d = gv + pull;
+                double mv = mu * (double)mi[p] + d;
+                mi[p] = (float)mv;
+                mv = (double)mi[p];
+                step = (flags & ORACLE_NESTEROV) ? d + mu * mv : mv;
+            }
+            xi[p] = (float)(xv - eta * step);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Matrix completion on observed entries.  Worker row = [U (m x r) | V (n x r)],
+ * both row-major.  For batch entries k with (a_k, b_k, M_k):
+ *   e_k = <U[a_k], V[b_k]> - M_k ; loss = c * sum e_k^2 ;
+ *   dU[a] = 2c * sum_{k: a_k=a} e_k V[b_k] ; dV[b] = 2c * sum_{k: b_k=b} e_k U[a_k].
+ * With every entry observed, U = V = X and c = 1/2 ... the problem family of
+ * the supplement's "Low-Rank Matrix Completion Experiments".           */
+/* ------------------------------------------------------------------ */
+void lsgd_oracle_mc_grad_loss(const float* x, int W, int64_t ld, int m, int n, int r,
+                              const int32_t* rows, const int32_t* cols, const float* vals,
+                              int64_t n_obs, const int32_t* batch_idx, int64_t B, float c_f,
+                              float* g, float* losses)
+{
+    const int64_t P = (int64_t)(m + n) * r;
+    const double c = c_f;
+    const int64_t nb = batch_idx ? B : n_obs;
+    #pragma omp parallel for schedule(static)
+    for (int i = 0; i < W; ++i) {
+        const float* U = x + (int64_t)i * ld;
+        const float* V = U + (int64_t)m * r;
+        double* acc = (double*)calloc((size_t)P, sizeof(double));
+        double* aU = acc;
+        double* aV = acc + (int64_t)m * r;
+        double loss = 0.0;
+        for (int64_t k = 0; k < nb; ++k) {
+            int64_t s = batch_idx ? batch_idx[(int64_t)i * B + k] : k;
+            int a = rows[s], b = cols[s];
+            double dot = 0.0;
+            for (int q = 0; q < r; ++q) dot += (double)U[(int64_t)a * r + q] * (double)V[(int64_t)b * r + q];
+            double e = dot - (double)vals[s];
+            loss += e * e;
+            for (int q = 0; q < r; ++q) {
+                aU[(int64_t)a * r + q] += e * (double)V[(int64_t)b * r + q];
+                aV[(int64_t)b * r + q] += e * (double)U[(int64_t)a * r + q];
+            }
+        }
+        float* gi = g + (int64_t)i * ld;
+        for (int64_t p = 0; p < P; ++p) gi[p] = (float)(2.0 * c * acc[p]);
+        for (int64_t p = P; p < ld; ++p) gi[p] = 0.0f;
+        losses[i] = (float)(c * loss);
+        free(acc);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* MLP classifier, softmax cross-entropy, mixed precision.
+ * Worker row = [W_1 (d1 x d0 row-major) | b_1 | W_2 | b_2 | ...].
+ * Rounding points (round-to-nearest-even to bf16): the inputs X (already
+ * stored as bf16), weight operands, stored activations h_k = relu(z_k), and
+ * back-propagated deltas used as matrix operands.  Biases, logits, softmax,
+ * loss, dW, db stay fp32 (fp64 accumulation here).                     */
+/* ------------------------------------------------------------------ */
+static float bf16_round(float v)
+{
+    uint32_t u; memcpy(&u, &v, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) return v;           /* inf / nan unchanged */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + lsb;
+    u &= 0xFFFF0000u;
+    float o; memcpy(&o, &u, 4);
+    return o;
+}
+static float bf16_bits_to_float(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16; float o; memcpy(&o, &u, 4); return o;
+}
+
+void lsgd_oracle_mlp_grad_loss(const float* x, int W, int64_t ld, int n_layers, const int32_t* dims,
+                               const uint16_t* X, const int32_t* y, int B,
+                               float* g, float* losses)
+{
+    const int L = n_layers;
+    int64_t P = 0;
+    for (int k = 0; k < L; ++k) P += (int64_t)dims[k + 1] * dims[k] + dims[k + 1];
+
+    #pragma omp parallel for schedule(dynamic, 1)
+    for (int i = 0; i < W; ++i) {
+        const float* xi = x + (int64_t)i * ld;
+        float* gi = g + (int64_t)i * ld;
+        /* per-layer buffers */
+        float** Wq = (float**)malloc(sizeof(float*) * L);     /* bf16-rounded weights  */
+        const float** bias = (const float**)malloc(sizeof(float*) * L);
+        float** h = (float**)malloc(sizeof(float*) * (L + 1)); /* h[0]=input, h[k] bf16 activations */
+        float** z = (float**)malloc(sizeof(float*) * (L + 1)); /* fp32 pre-activations  */
+        int64_t* woff = (int64_t*)malloc(sizeof(int64_t) * L);
+        int64_t o = 0;
+        for (int k = 0; k < L; ++k) {
+            int64_t nw = (int64_t)dims[k + 1] * dims[k];
+            woff[k] = o;
+            Wq[k] = (float*)malloc(sizeof(float) * nw);
+            for (int64_t t = 0; t < nw; ++t) Wq[k][t] = bf16_round(xi[o + t]);
+            bias[k] = xi + o + nw;
+            o += nw + dims[k + 1];
+        }
+        h[0] = (float*)malloc(sizeof(float) * (size_t)B * dims[0]);
+        z[0] = 0;
+        for (int64_t t = 0; t < (int64_t)B * dims[0]; ++t)
+            h[0][t] = bf16_bits_to_float(X[(int64_t)i * B * dims[0] + t]);
+
+        /* forward */
+        for (int k = 0; k < L; ++k) {
+            int din = dims[k], dout = dims[k + 1];
+            z[k + 1] = (float*)malloc(sizeof(float) * (size_t)B * dout);
+            h[k + 1] = (float*)malloc(sizeof(float) * (size_t)B * dout);
+            for (int b = 0; b < B; ++b)
+                for (int q = 0; q < dout; ++q) {
+                    double acc = 0.0;
+                    const float* hr = h[k] + (int64_t)b * din;
+                    const float* wr = Wq[k] + (int64_t)q * din;
+                    for (int p = 0; p < din; ++p) acc += (double)hr[p] * (double)wr[p];
+                    float zz = (float)(acc + (double)bias[k][q]);
+                    z[k + 1][(int64_t)b * dout + q] = zz;
+                    h[k + 1][(int64_t)b * dout + q] = (k + 1 < L) ? bf16_round(zz > 0.0f ? zz : 0.0f) : zz;
+                }
+        }
+        /* loss and output delta */
+        int C = dims[L];
+        double loss = 0.0;
+        float* delta = (float*)malloc(sizeof(float) * (size_t)B * C);
+        for (int b = 0; b < B; ++b) {
+            const float* lg = z[L] + (int64_t)b * C;
+            double mx = lg[0];
+            for (int q = 1; q < C; ++q) if ((double)lg[q] > mx) mx = lg[q];
+            double se = 0.0;
+            for (int q = 0; q < C; ++q) se += exp((double)lg[q] - mx);
+            double lse = mx + log(se);
+            int yb = y[(int64_t)i * B + b];
+            loss += lse - (double)lg[yb];
+            for (int q = 0; q < C; ++q) {
+                double pq = exp((double)lg[q] - lse);
+                double d = (pq - (q == yb ? 1.0 : 0.0)) / (double)B;
+                delta[(int64_t)b * C + q] = bf16_round((float)d);
+            }
+        }
+        losses[i] = (float)(loss / (double)B);
+
+        /* backward */
+        for (int k = L - 1; k >= 0; --k) {
+            int din = dims[k], dout = dims[k + 1];
+            int64_t nw = (int64_t)din * dout;
+            double* acc = (double*)calloc((size_t)nw, sizeof(double));
+            double* accb = (double*)calloc((size_t)dout, sizeof(double));
+            for (int b = 0; b < B; ++b)
+                for (int q = 0; q < dout; ++q) {
+                    double d = delta[(int64_t)b * dout + q];
+                    accb[q] += d;
+                    if (d == 0.0) continue;
+                    const float* hr = h[k] + (int64_t)b * din;
+                    double* ar = acc + (int64_t)q * din;
+                    for (int p = 0; p < din; ++p) ar[p] += d * (double)hr[p];
+                }
+            for (int64_t t = 0; t < nw; ++t) gi[woff[k] + t] = (float)acc[t];
+            for (int q = 0; q < dout; ++q) gi[woff[k] + nw + q] = (float)accb[q];
+            free(acc); free(accb);
+            if (k > 0) {
+                float* nd = (float*)malloc(sizeof(float) * (size_t)B * din);
+                for (int b = 0; b < B; ++b)
+                    for (int p = 0; p < din; ++p) {
+                        double s = 0.0;
+                        for (int q = 0; q < dout; ++q)
+                            s += (double)delta[(int64_t)b * dout + q] * (double)Wq[k][(int64_t)q * din + p];
+                        float sv = (float)s;
+                        nd[(int64_t)b * din + p] = (z[k][(int64_t)b * din + p] > 0.0f) ? bf16_round(sv) : 0.0f;
+                    }
+                free(delta);
+                delta = nd;
+            }
+        }
+        for (int64_t p = P; p < ld; ++p) gi[p] = 0.0f;
+        free(delta);
+        for (int k = 0; k < L; ++k) free(Wq[k]);
+        for (int k = 0; k <= L; ++k) { free(h[k]); if (z[k]) free(z[k]); }
+        free(Wq); free(bias); free(h); free(z); free(woff);
+    }
+}
+
+/* Loss only (forward pass in the same arithmetic), for finite-difference pins
+ * on a model whose weights/activations are exactly bf16-representable.   */
+float lsgd_oracle_bf16_round(float v) { return bf16_round(v); }
