@@ -1,0 +1,191 @@
+/*
+ * lsgd.h - C boundary of the batched Leader-SGD step for one AMD MI355X (gfx950).
+ *
+ * A population of W workers lives on one GPU as a row-major fp32 matrix
+ * x[W, ld] (row i = parameters of worker i, P <= ld used columns).  Workers are
+ * partitioned into n contiguous groups (Eq. 2 of arXiv 1905.10395: n groups of
+ * l workers, each with a local leader, plus one global leader).  One step is
+ *
+ *   1. lsgd_grad_loss       g_i, loss_i of every worker on its own minibatch
+ *                           (Section 2: stochastic gradient g_t^{j,i}; Section
+ *                           3.1.3: one loss sample per worker)
+ *   2. lsgd_select_leaders  segmented argmin of the losses (Eq. 1 / Eq. 2;
+ *                           Algorithm 1 "determine the local / global best")
+ *   3. lsgd_pull_update     x_i <- x_i - eta*(g_i + lam_L (x_i - z_local)
+ *                                              + lam_G (x_i - z_global))
+ *                           (supplement B.1; Eq. 3), optional momentum
+ *   lsgd_step               1-3 on the population's stream, no host sync.
+ *
+ * General rules
+ *   - Pointers marked "device" are device memory owned by the caller for the
+ *     life of the handle; the library never allocates, frees or resizes them.
+ *     Pointers marked "host" are read during the call only.
+ *   - Every call validates its arguments first; a failing call enqueues no
+ *     device work.  Calls return an lsgd_status and never abort or throw;
+ *     lsgd_last_error() gives a message for the last failure on this thread.
+ *   - All device work is enqueued on the stream given at creation.  Only
+ *     lsgd_get_leaders / lsgd_get_losses synchronise that stream.
+ *   - Worker indices returned are global, in [0, W).
+ */
+#ifndef LSGD_H
+#define LSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lsgd_population lsgd_population; /* opaque host object */
+
+typedef enum {
+    LSGD_OK = 0,
+    LSGD_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, bad enum, non-finite scalar */
+    LSGD_ERR_SHAPE = 2,       /* W<=0, ld<P, offsets not covering [0,W], sizes not matching P  */
+    LSGD_ERR_STATE = 3,       /* call order: pull with lam>0 before any selection, missing buffer */
+    LSGD_ERR_UNSUPPORTED = 4, /* shape outside what the kernels implement                       */
+    LSGD_ERR_HIP = 5,         /* a HIP runtime call failed                                      */
+    LSGD_ERR_NOMEM = 6        /* workspace too small / host allocation failed                   */
+} lsgd_status;
+
+/* lsgd_config.flags */
+enum {
+    LSGD_NESTEROV = 1,            /* x <- x - eta*(d + mu*m) instead of x <- x - eta*m            */
+    LSGD_LEADER_EXEMPT = 2,       /* a leader is not pulled to a (stale) copy of itself:
+                                     supplement, lemma on leader descent                          */
+    LSGD_PULL_UNSCALED_BY_ETA = 4,/* Eq. 3 as printed: pulls are not multiplied by eta            */
+    LSGD_MOMENTUM_GRAD_ONLY = 8,  /* momentum buffer accumulates g only; pulls applied outside it */
+    LSGD_WRITE_BF16_SHADOW = 16   /* pull_update also writes bf16(x) to x_bf16 (MLP operands)     */
+};
+
+#define LSGD_MAX_WORKERS 65536
+#define LSGD_MAX_GROUPS 1024
+
+typedef struct {
+    int32_t W;                    /* workers = rows                                              */
+    int64_t P;                    /* parameters per worker                                       */
+    int64_t ld;                   /* row stride in elements, ld >= P                             */
+    int32_t n_groups;             /* n of Eq. 2                                                  */
+    const int32_t* group_offsets; /* host [n_groups+1], strictly increasing, [0]=0, [n]=W;
+                                     NULL: W % n_groups == 0 and equal contiguous groups          */
+    float momentum;               /* mu; 0 disables the momentum buffer                          */
+    int32_t flags;                /* LSGD_* bits above                                           */
+    float weight_decay;           /* g <- g + wd*x inside the update; 0 = none                   */
+} lsgd_config;
+
+/* ---- minibatch descriptors (host structs; the arrays they point to are device memory) ---- */
+typedef enum { LSGD_BATCH_EXTERNAL = 0, LSGD_BATCH_MC = 1, LSGD_BATCH_MLP = 2 } lsgd_batch_kind;
+
+/* Gradient and losses were produced by the caller: g (given at creation) is
+ * already filled; losses is device [W].                                        */
+typedef struct {
+    const float* losses; /* device [W] */
+} lsgd_external_batch;
+
+/* Low-rank matrix completion on observed entries (the problem family of the
+ * paper's motivating example and supplement, rectangular form).  Worker row =
+ * [U (m x r, row-major) | V (n x r, row-major)], P = (m+n)*r.  For each batch
+ * entry k = (a_k, b_k, M_k): e_k = <U[a_k],V[b_k]> - M_k;
+ * loss = c*sum e_k^2; dU[a] = 2c*sum_{a_k=a} e_k V[b_k]; dV[b] likewise.
+ * Entries drawn more than once count each time.                                */
+typedef struct {
+    int32_t m, n, r;
+    const int32_t* rows;      /* device [n_obs] row index a of each observed entry  */
+    const int32_t* cols;      /* device [n_obs] column index b                      */
+    const float* vals;        /* device [n_obs] observed value M_ab                 */
+    int64_t n_obs;
+    const int32_t* batch_idx; /* device [W, B] indices into the observed list, or
+                                 NULL: every worker uses all n_obs entries (batch
+                                 gradient, "LGD")                                   */
+    int64_t B;                /* entries per worker when batch_idx != NULL          */
+    float c;                  /* loss normalisation                                 */
+} lsgd_mc_batch;
+
+/* Fully connected ReLU classifier with softmax cross-entropy, mean over the
+ * batch.  Worker row = [W_1 (d1 x d0 row-major) | b_1 | W_2 | b_2 | ...].
+ * Matrix operands (inputs, weights, stored activations, back-propagated
+ * deltas) are bf16, accumulation and everything else fp32.                     */
+typedef struct {
+    int32_t n_layers;    /* number of weight matrices                              */
+    const int32_t* dims; /* host [n_layers+1]: d0 (input) ... d_L (classes)        */
+    const uint16_t* X;   /* device [W, B, d0] bf16 bit patterns                    */
+    const int32_t* y;    /* device [W, B] class labels in [0, d_L)                 */
+    int32_t B;           /* samples per worker                                     */
+} lsgd_mlp_batch;
+
+typedef struct {
+    int32_t kind;     /* lsgd_batch_kind                                            */
+    const void* desc; /* host pointer to the matching struct above                  */
+} lsgd_batch;
+
+/* Bytes of device workspace lsgd_create_population needs for this population
+ * and for gradient calls shaped like `largest` (NULL: selection and update
+ * only).  Returns 0 on invalid arguments (see lsgd_last_error).               */
+size_t lsgd_workspace_bytes(const lsgd_config* cfg, const lsgd_batch* largest);
+
+/* Binds caller-owned device buffers into a population handle.
+ *   x, g       device [W, ld] fp32, required
+ *   m          device [W, ld] fp32, required iff cfg->momentum != 0; the caller zeroes it
+ *   z_snapshot device [(n_groups+1), ld] fp32 leader copies kept between
+ *              communications (Algorithm 1; supplement B.1).  NULL is allowed
+ *              when every update follows a full refresh.
+ *   x_bf16     device [W, ld] bf16, required for LSGD_BATCH_MLP and for
+ *              LSGD_WRITE_BF16_SHADOW, else NULL
+ *   workspace  device, >= lsgd_workspace_bytes(...), 256-byte aligned
+ *   hip_stream a hipStream_t (NULL = default stream)
+ * The fast update path needs x, g, m, z_snapshot 16-byte aligned and ld % 4 == 0;
+ * other layouts take a scalar path.                                            */
+lsgd_status lsgd_create_population(const lsgd_config* cfg, float* x, float* g, float* m,
+                                   float* z_snapshot, uint16_t* x_bf16, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream,
+                                   lsgd_population** out);
+
+/* Frees the host object only. */
+lsgd_status lsgd_destroy_population(lsgd_population* pop);
+
+/* Writes g[W, ld] (unused padding columns zeroed) and losses (device [W]; NULL =
+ * the population's own loss buffer, the one lsgd_step uses).  For
+ * LSGD_BATCH_EXTERNAL copies the given losses into the population's buffer when
+ * `losses` is NULL, otherwise into `losses`.                                   */
+lsgd_status lsgd_grad_loss(lsgd_population* pop, const lsgd_batch* batch, float* losses);
+
+/* Segmented argmin.  For each group j with refresh_local[j] != 0 (host
+ * [n_groups]; NULL = all) the local leader becomes the lowest index attaining the
+ * group's minimum loss; if refresh_global the global leader becomes the lowest
+ * index attaining the minimum over all workers.  NaN counts as +infinity.  The
+ * leaders refreshed here are captured (copied from x before any row changes) by
+ * the next lsgd_pull_update; the others keep their stored copies.
+ * losses: device [W]; NULL = the population's own buffer.                       */
+lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses,
+                                const uint8_t* refresh_local, int refresh_global);
+
+/* d = g + wd*x + lam_L (x - z_local) + lam_G (x - z_global);
+ * mu = 0: x <- x - eta*d;  mu > 0: m <- mu*m + d, x <- x - eta*m (flags modify).
+ * In place on x and m; every row is computed from pre-update values.  A term
+ * whose coefficient is exactly 0 is skipped and its leader copy is neither read
+ * nor written.  LSGD_ERR_STATE if a needed leader was never selected, or a kept
+ * copy is needed and z_snapshot is NULL.                                        */
+lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, float lambda_G);
+
+/* grad_loss -> select_leaders -> pull_update with the population's own loss
+ * buffer.  The first step of a population must refresh everything.            */
+lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, float lambda_L,
+                      float lambda_G, const uint8_t* refresh_local, int refresh_global);
+
+/* Recomputes the whole bf16 shadow from x (after the caller changed x). */
+lsgd_status lsgd_sync_shadow(lsgd_population* pop);
+
+/* Synchronise the stream and read back.  local_leaders: host [n_groups];
+ * global_leader: host [1]; either may be NULL.  Leaders never selected read -1. */
+lsgd_status lsgd_get_leaders(lsgd_population* pop, int32_t* local_leaders, int32_t* global_leader);
+/* losses_host: host [W], the population's own loss buffer. */
+lsgd_status lsgd_get_losses(lsgd_population* pop, float* losses_host);
+
+/* Message for the last failing call on this thread ("" if none).  Static storage. */
+const char* lsgd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSGD_H */

@@ -1,0 +1,448 @@
+// Host side of the C boundary declared in lsgd.h: argument validation, the
+// population object, workspace carving and kernel dispatch.  No arithmetic of
+// the method lives here.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace lsgd;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+lsgd_status fail(lsgd_status st, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t lead, glead, refreshed, offsets, group_of, losses, partials, scratch, total;
+    size_t partials_cap, scratch_bytes;
+};
+
+Layout make_layout(int W, int G, size_t partials_cap, size_t scratch_bytes)
+{
+    Layout L;
+    size_t o = 0;
+    L.lead = o;      o = align_up(o + sizeof(int32_t) * (size_t)G);
+    L.glead = o;     o = align_up(o + sizeof(int32_t));
+    L.refreshed = o; o = align_up(o + sizeof(int32_t) * (size_t)(G + 1));
+    L.offsets = o;   o = align_up(o + sizeof(int32_t) * (size_t)(G + 1));
+    L.group_of = o;  o = align_up(o + sizeof(int32_t) * (size_t)W);
+    L.losses = o;    o = align_up(o + sizeof(float) * (size_t)W);
+    L.partials = o;  o = align_up(o + sizeof(float) * partials_cap);
+    L.scratch = o;   o = align_up(o + scratch_bytes);
+    L.total = o;
+    L.partials_cap = partials_cap;
+    L.scratch_bytes = scratch_bytes;
+    return L;
+}
+
+lsgd_status check_config(const lsgd_config* cfg, std::vector<int32_t>* offsets_out)
+{
+    if (!cfg) return fail(LSGD_ERR_INVALID_ARG, "config is NULL");
+    if (cfg->W <= 0 || cfg->W > LSGD_MAX_WORKERS) return fail(LSGD_ERR_SHAPE, "W=%d outside [1,%d]", cfg->W, LSGD_MAX_WORKERS);
+    if (cfg->P <= 0) return fail(LSGD_ERR_SHAPE, "P=%lld must be positive", (long long)cfg->P);
+    if (cfg->ld < cfg->P) return fail(LSGD_ERR_SHAPE, "ld=%lld < P=%lld", (long long)cfg->ld, (long long)cfg->P);
+    if (cfg->n_groups <= 0 || cfg->n_groups > LSGD_MAX_GROUPS || cfg->n_groups > cfg->W)
+        return fail(LSGD_ERR_SHAPE, "n_groups=%d outside [1,min(W,%d)]", cfg->n_groups, LSGD_MAX_GROUPS);
+    if (!std::isfinite(cfg->momentum) || cfg->momentum < 0.0f) return fail(LSGD_ERR_INVALID_ARG, "momentum must be finite and >= 0");
+    if (!std::isfinite(cfg->weight_decay)) return fail(LSGD_ERR_INVALID_ARG, "weight_decay must be finite");
+    const int known = LSGD_NESTEROV | LSGD_LEADER_EXEMPT | LSGD_PULL_UNSCALED_BY_ETA | LSGD_MOMENTUM_GRAD_ONLY | LSGD_WRITE_BF16_SHADOW;
+    if (cfg->flags & ~known) return fail(LSGD_ERR_INVALID_ARG, "unknown flag bits 0x%x", cfg->flags & ~known);
+    std::vector<int32_t> off((size_t)cfg->n_groups + 1);
+    if (cfg->group_offsets) {
+        for (int j = 0; j <= cfg->n_groups; ++j) off[(size_t)j] = cfg->group_offsets[j];
+        if (off.front() != 0 || off.back() != cfg->W) return fail(LSGD_ERR_SHAPE, "group_offsets must start at 0 and end at W");
+        for (int j = 0; j < cfg->n_groups; ++j)
+            if (off[(size_t)j + 1] <= off[(size_t)j]) return fail(LSGD_ERR_SHAPE, "group %d is empty or offsets decrease", j);
+    } else {
+        if (cfg->W % cfg->n_groups) return fail(LSGD_ERR_SHAPE, "W=%d not divisible by n_groups=%d and no group_offsets", cfg->W, cfg->n_groups);
+        for (int j = 0; j <= cfg->n_groups; ++j) off[(size_t)j] = j * (cfg->W / cfg->n_groups);
+    }
+    if (offsets_out) offsets_out->swap(off);
+    return LSGD_OK;
+}
+
+int64_t mlp_params(const lsgd_mlp_batch& b)
+{
+    int64_t P = 0;
+    for (int k = 0; k < b.n_layers; ++k) P += (int64_t)b.dims[k + 1] * b.dims[k] + b.dims[k + 1];
+    return P;
+}
+
+// Shape/pointer checks of a batch against a population shape; also sizes its scratch needs.
+lsgd_status check_batch(const lsgd_batch* batch, int W, int64_t P, size_t* partials, size_t* scratch)
+{
+    if (partials) *partials = 0;
+    if (scratch) *scratch = 0;
+    if (!batch) return fail(LSGD_ERR_INVALID_ARG, "batch is NULL");
+    if (!batch->desc) return fail(LSGD_ERR_INVALID_ARG, "batch->desc is NULL");
+    switch (batch->kind) {
+    case LSGD_BATCH_EXTERNAL: {
+        const auto* d = static_cast<const lsgd_external_batch*>(batch->desc);
+        if (!d->losses) return fail(LSGD_ERR_INVALID_ARG, "external batch: losses is NULL");
+        return LSGD_OK;
+    }
+    case LSGD_BATCH_MC: {
+        const auto* d = static_cast<const lsgd_mc_batch*>(batch->desc);
+        if (d->m <= 0 || d->n <= 0 || d->r <= 0) return fail(LSGD_ERR_SHAPE, "matrix completion: m, n, r must be positive");
+        if ((int64_t)(d->m + (int64_t)d->n) * d->r != P)
+            return fail(LSGD_ERR_SHAPE, "matrix completion: (m+n)*r = %lld != P = %lld", (long long)((int64_t)(d->m + (int64_t)d->n) * d->r), (long long)P);
+        if (d->n_obs < 0 || d->B < 0) return fail(LSGD_ERR_SHAPE, "matrix completion: negative n_obs or B");
+        if (d->n_obs > 0 && (!d->rows || !d->cols || !d->vals)) return fail(LSGD_ERR_INVALID_ARG, "matrix completion: rows/cols/vals is NULL");
+        if (d->batch_idx && d->B > 0 && d->n_obs == 0) return fail(LSGD_ERR_SHAPE, "matrix completion: batch indices into an empty list");
+        if (!std::isfinite(d->c)) return fail(LSGD_ERR_INVALID_ARG, "matrix completion: c must be finite");
+        if (partials) *partials = mc_partials(W, *d);
+        if (scratch) *scratch = mc_scratch_bytes(W, *d);
+        return LSGD_OK;
+    }
+    case LSGD_BATCH_MLP: {
+        const auto* d = static_cast<const lsgd_mlp_batch*>(batch->desc);
+        if (d->n_layers <= 0 || !d->dims) return fail(LSGD_ERR_INVALID_ARG, "MLP: n_layers must be positive and dims non-NULL");
+        for (int k = 0; k <= d->n_layers; ++k)
+            if (d->dims[k] <= 0) return fail(LSGD_ERR_SHAPE, "MLP: dims[%d] must be positive", k);
+        if (mlp_params(*d) != P) return fail(LSGD_ERR_SHAPE, "MLP: layer sizes give %lld parameters, P = %lld", (long long)mlp_params(*d), (long long)P);
+        if (d->B <= 0) return fail(LSGD_ERR_SHAPE, "MLP: B must be positive");
+        if (!d->X || !d->y) return fail(LSGD_ERR_INVALID_ARG, "MLP: X or y is NULL");
+        const char* why = "";
+        if (!mlp_shape_supported(*d, &why)) return fail(LSGD_ERR_UNSUPPORTED, "MLP: %s", why);
+        if (scratch) *scratch = mlp_scratch_bytes(W, *d);
+        return LSGD_OK;
+    }
+    default:
+        return fail(LSGD_ERR_INVALID_ARG, "unknown batch kind %d", batch->kind);
+    }
+}
+
+} // namespace
+
+struct lsgd_population {
+    lsgd_config cfg;
+    std::vector<int32_t> offsets, group_of;
+    float *x, *g, *m, *Z;
+    uint16_t* xb;
+    hipStream_t stream;
+    Layout layout;
+    DeviceState st;
+    std::vector<uint8_t> local_selected, pending_local, z_valid; // z_valid: [G+1]
+    bool global_selected, pending_global;
+    bool shadow_valid;
+};
+
+extern "C" {
+
+const char* lsgd_last_error(void) { return g_err; }
+
+size_t lsgd_workspace_bytes(const lsgd_config* cfg, const lsgd_batch* largest)
+{
+    if (check_config(cfg, nullptr) != LSGD_OK) return 0;
+    size_t partials = 0, scratch = 0;
+    if (largest && check_batch(largest, cfg->W, cfg->P, &partials, &scratch) != LSGD_OK) return 0;
+    // fixed part (with a W-float partials slot), then oversized partials, then workload scratch
+    size_t total = make_layout(cfg->W, cfg->n_groups, (size_t)cfg->W, 0).total;
+    if (partials > (size_t)cfg->W) total += align_up(sizeof(float) * partials);
+    return total + align_up(scratch);
+}
+
+lsgd_status lsgd_create_population(const lsgd_config* cfg, float* x, float* g, float* m, float* z_snapshot,
+                                   uint16_t* x_bf16, void* workspace, size_t workspace_bytes, void* hip_stream,
+                                   lsgd_population** out)
+{
+    if (!out) return fail(LSGD_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    std::vector<int32_t> off;
+    lsgd_status st = check_config(cfg, &off);
+    if (st != LSGD_OK) return st;
+    if (!x || !g) return fail(LSGD_ERR_INVALID_ARG, "x and g are required");
+    if (cfg->momentum != 0.0f && !m) return fail(LSGD_ERR_INVALID_ARG, "momentum != 0 needs the m buffer");
+    if ((cfg->flags & LSGD_WRITE_BF16_SHADOW) && !x_bf16) return fail(LSGD_ERR_INVALID_ARG, "LSGD_WRITE_BF16_SHADOW needs x_bf16");
+    if (!workspace) return fail(LSGD_ERR_INVALID_ARG, "workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return fail(LSGD_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    const size_t fixed = make_layout(cfg->W, cfg->n_groups, (size_t)cfg->W, 0).total;
+    if (workspace_bytes < fixed) return fail(LSGD_ERR_NOMEM, "workspace of %zu bytes < %zu needed", workspace_bytes, fixed);
+
+    lsgd_population* p = new (std::nothrow) lsgd_population();
+    if (!p) return fail(LSGD_ERR_NOMEM, "host allocation failed");
+    p->cfg = *cfg;
+    p->cfg.group_offsets = nullptr;
+    p->offsets = off;
+    p->group_of.resize((size_t)cfg->W);
+    for (int j = 0; j < cfg->n_groups; ++j)
+        for (int i = off[(size_t)j]; i < off[(size_t)j + 1]; ++i) p->group_of[(size_t)i] = j;
+    p->x = x; p->g = g; p->m = m; p->Z = z_snapshot; p->xb = x_bf16;
+    p->stream = static_cast<hipStream_t>(hip_stream);
+    // everything past the fixed part is split between loss partials and workload scratch on demand
+    const size_t spare = workspace_bytes - fixed;
+    p->layout = make_layout(cfg->W, cfg->n_groups, (size_t)cfg->W, 0);
+    char* base = static_cast<char*>(workspace);
+    p->st.lead = reinterpret_cast<int32_t*>(base + p->layout.lead);
+    p->st.glead = reinterpret_cast<int32_t*>(base + p->layout.glead);
+    p->st.refreshed = reinterpret_cast<int32_t*>(base + p->layout.refreshed);
+    p->st.offsets = reinterpret_cast<int32_t*>(base + p->layout.offsets);
+    p->st.group_of = reinterpret_cast<int32_t*>(base + p->layout.group_of);
+    p->st.losses = reinterpret_cast<float*>(base + p->layout.losses);
+    p->st.partials = reinterpret_cast<float*>(base + p->layout.partials);
+    p->st.partials_cap = (size_t)cfg->W;
+    p->st.scratch = base + p->layout.total;
+    p->st.scratch_bytes = spare;
+    p->local_selected.assign((size_t)cfg->n_groups, 0);
+    p->pending_local.assign((size_t)cfg->n_groups, 0);
+    p->z_valid.assign((size_t)cfg->n_groups + 1, 0);
+    p->global_selected = p->pending_global = false;
+    p->shadow_valid = false;
+
+    hipError_t e = hipMemcpyAsync(p->st.offsets, p->offsets.data(), sizeof(int32_t) * p->offsets.size(), hipMemcpyHostToDevice, p->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(p->st.group_of, p->group_of.data(), sizeof(int32_t) * p->group_of.size(), hipMemcpyHostToDevice, p->stream);
+    if (e == hipSuccess) e = launch_init_state(p->st, cfg->W, cfg->n_groups, p->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(p->stream); // host vectors were the copy source
+    if (e != hipSuccess) {
+        delete p;
+        return fail(LSGD_ERR_HIP, "create: %s", hipGetErrorString(e));
+    }
+    *out = p;
+    return LSGD_OK;
+}
+
+lsgd_status lsgd_destroy_population(lsgd_population* pop)
+{
+    delete pop;
+    return LSGD_OK;
+}
+
+} // extern "C"
+
+namespace {
+
+lsgd_status do_grad_loss(lsgd_population* p, const lsgd_batch* batch, float* losses_out)
+{
+    float* losses = losses_out ? losses_out : p->st.losses;
+    hipError_t e = hipSuccess;
+    switch (batch->kind) {
+    case LSGD_BATCH_EXTERNAL: {
+        const auto* d = static_cast<const lsgd_external_batch*>(batch->desc);
+        if (d->losses != losses)
+            e = hipMemcpyAsync(losses, d->losses, sizeof(float) * (size_t)p->cfg.W, hipMemcpyDeviceToDevice, p->stream);
+        break;
+    }
+    case LSGD_BATCH_MC: {
+        const auto* d = static_cast<const lsgd_mc_batch*>(batch->desc);
+        // loss partials live at the start of the spare region when they outgrow the fixed slot
+        DeviceState st = p->st;
+        const size_t need = mc_partials(p->cfg.W, *d);
+        size_t used = 0;
+        if (need > (size_t)p->cfg.W) {
+            st.partials = reinterpret_cast<float*>(p->st.scratch);
+            used = align_up(sizeof(float) * need);
+        }
+        st.scratch = p->st.scratch + used;
+        st.scratch_bytes = p->st.scratch_bytes - used;
+        e = launch_mc_grad_loss(p->x, p->g, losses, p->cfg.W, p->cfg.P, p->cfg.ld, *d, st, p->stream);
+        break;
+    }
+    case LSGD_BATCH_MLP: {
+        const auto* d = static_cast<const lsgd_mlp_batch*>(batch->desc);
+        if (!p->shadow_valid) {
+            e = launch_cast_shadow(p->x, p->xb, p->cfg.W, p->cfg.P, p->cfg.ld, p->stream);
+            if (e != hipSuccess) break;
+            p->shadow_valid = true;
+        }
+        e = launch_mlp_grad_loss(p->xb, p->x, p->g, losses, p->cfg.W, p->cfg.P, p->cfg.ld, *d, p->st, p->stream);
+        break;
+    }
+    default: break;
+    }
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "grad_loss: %s", hipGetErrorString(e));
+    return LSGD_OK;
+}
+
+lsgd_status check_grad_loss(lsgd_population* p, const lsgd_batch* batch)
+{
+    size_t partials = 0, scratch = 0;
+    lsgd_status st = check_batch(batch, p->cfg.W, p->cfg.P, &partials, &scratch);
+    if (st != LSGD_OK) return st;
+    if (batch->kind == LSGD_BATCH_MLP && !p->xb) return fail(LSGD_ERR_STATE, "MLP batches need the x_bf16 buffer");
+    size_t need = scratch;
+    if (partials > (size_t)p->cfg.W) need += align_up(sizeof(float) * partials);
+    if (need > p->st.scratch_bytes)
+        return fail(LSGD_ERR_NOMEM, "workspace too small for this batch: %zu spare bytes, %zu needed", p->st.scratch_bytes, need);
+    return LSGD_OK;
+}
+
+lsgd_status check_scalars(float eta, float lamL, float lamG)
+{
+    if (!std::isfinite(eta) || !std::isfinite(lamL) || !std::isfinite(lamG))
+        return fail(LSGD_ERR_INVALID_ARG, "eta, lambda_L, lambda_G must be finite");
+    return LSGD_OK;
+}
+
+// Would an update with these coefficients find every leader it needs, given
+// what is selected / pending / kept (optionally after a selection with this mask)?
+lsgd_status check_pull_state(const lsgd_population* p, float eta, float lamL, float lamG,
+                             const uint8_t* extra_local, bool extra_all_local, bool extra_global)
+{
+    if ((p->cfg.flags & LSGD_PULL_UNSCALED_BY_ETA) && (lamL != 0.0f || lamG != 0.0f) && eta == 0.0f)
+        return fail(LSGD_ERR_INVALID_ARG, "unscaled pulls need eta != 0");
+    const int G = p->cfg.n_groups;
+    if (lamL != 0.0f) {
+        for (int j = 0; j < G; ++j) {
+            const bool fresh = p->pending_local[(size_t)j] || extra_all_local || (extra_local && extra_local[j]);
+            if (fresh) continue;
+            if (!p->Z) return fail(LSGD_ERR_STATE, "group %d keeps its leader but z_snapshot is NULL", j);
+            if (!p->z_valid[(size_t)j]) return fail(LSGD_ERR_STATE, "group %d has no selected leader copy", j);
+        }
+    }
+    if (lamG != 0.0f) {
+        const bool fresh = p->pending_global || extra_global;
+        if (!fresh) {
+            if (!p->Z) return fail(LSGD_ERR_STATE, "global leader is kept but z_snapshot is NULL");
+            if (!p->z_valid[(size_t)G]) return fail(LSGD_ERR_STATE, "no global leader copy has been selected");
+        }
+    }
+    return LSGD_OK;
+}
+
+lsgd_status do_select(lsgd_population* p, const float* losses, const uint8_t* refresh_local, int refresh_global)
+{
+    const int G = p->cfg.n_groups;
+    RefreshBits sel, cap;
+    std::memset(&sel, 0, sizeof(sel));
+    std::memset(&cap, 0, sizeof(cap));
+    for (int j = 0; j < G; ++j) {
+        const bool r = !refresh_local || refresh_local[j];
+        if (r) {
+            sel.w[j >> 6] |= 1ull << (j & 63);
+            p->pending_local[(size_t)j] = 1;
+            p->local_selected[(size_t)j] = 1;
+        }
+        if (p->pending_local[(size_t)j]) cap.w[j >> 6] |= 1ull << (j & 63);
+    }
+    if (refresh_global) { p->pending_global = true; p->global_selected = true; }
+    hipError_t e = launch_select_leaders(losses ? losses : p->st.losses, p->cfg.W, G, p->st, sel, cap,
+                                         refresh_global != 0, p->pending_global, p->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "select_leaders: %s", hipGetErrorString(e));
+    return LSGD_OK;
+}
+
+lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG)
+{
+    const int G = p->cfg.n_groups;
+    PullParams q;
+    q.x = p->x; q.g = p->g; q.m = p->m; q.Z = p->Z;
+    q.xb = (p->cfg.flags & LSGD_WRITE_BF16_SHADOW) ? p->xb : nullptr;
+    q.P = p->cfg.P; q.ld = p->cfg.ld; q.W = p->cfg.W; q.G = G;
+    q.eta = eta; q.mu = p->cfg.momentum; q.wd = p->cfg.weight_decay;
+    q.lamL = lamL; q.lamG = lamG;
+    if (p->cfg.flags & LSGD_PULL_UNSCALED_BY_ETA) {
+        if (lamL != 0.0f) q.lamL = lamL / eta;
+        if (lamG != 0.0f) q.lamG = lamG / eta;
+    }
+    q.flags = p->cfg.flags;
+    bool any_pending = p->pending_global;
+    for (int j = 0; j < G; ++j) any_pending = any_pending || p->pending_local[(size_t)j];
+    q.use_refreshed = any_pending ? 1 : 0;
+    q.clear_refreshed = 0;
+    hipError_t e = launch_pull_update(q, p->st, p->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "pull_update: %s", hipGetErrorString(e));
+    // a refreshed leader whose term was active has now been captured (and kept, if Z exists)
+    for (int j = 0; j < G; ++j) {
+        if (p->pending_local[(size_t)j] && lamL != 0.0f) p->z_valid[(size_t)j] = p->Z != nullptr;
+        p->pending_local[(size_t)j] = 0;
+    }
+    if (p->pending_global && lamG != 0.0f) p->z_valid[(size_t)G] = p->Z != nullptr;
+    p->pending_global = false;
+    if (!(p->cfg.flags & LSGD_WRITE_BF16_SHADOW)) p->shadow_valid = false;
+    return LSGD_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+lsgd_status lsgd_grad_loss(lsgd_population* pop, const lsgd_batch* batch, float* losses)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    lsgd_status st = check_grad_loss(pop, batch);
+    if (st != LSGD_OK) return st;
+    return do_grad_loss(pop, batch, losses);
+}
+
+lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses, const uint8_t* refresh_local, int refresh_global)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    return do_select(pop, losses, refresh_local, refresh_global);
+}
+
+lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, float lambda_G)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    lsgd_status st = check_scalars(eta, lambda_L, lambda_G);
+    if (st != LSGD_OK) return st;
+    st = check_pull_state(pop, eta, lambda_L, lambda_G, nullptr, false, false);
+    if (st != LSGD_OK) return st;
+    return do_pull(pop, eta, lambda_L, lambda_G);
+}
+
+lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, float lambda_L, float lambda_G,
+                      const uint8_t* refresh_local, int refresh_global)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    lsgd_status st = check_scalars(eta, lambda_L, lambda_G);
+    if (st != LSGD_OK) return st;
+    st = check_grad_loss(pop, batch);
+    if (st != LSGD_OK) return st;
+    st = check_pull_state(pop, eta, lambda_L, lambda_G, refresh_local, refresh_local == nullptr, refresh_global != 0);
+    if (st != LSGD_OK) return st;
+    st = do_grad_loss(pop, batch, nullptr);
+    if (st != LSGD_OK) return st;
+    st = do_select(pop, nullptr, refresh_local, refresh_global);
+    if (st != LSGD_OK) return st;
+    return do_pull(pop, eta, lambda_L, lambda_G);
+}
+
+lsgd_status lsgd_sync_shadow(lsgd_population* pop)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!pop->xb) return fail(LSGD_ERR_STATE, "no x_bf16 buffer was given");
+    hipError_t e = launch_cast_shadow(pop->x, pop->xb, pop->cfg.W, pop->cfg.P, pop->cfg.ld, pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "sync_shadow: %s", hipGetErrorString(e));
+    pop->shadow_valid = true;
+    return LSGD_OK;
+}
+
+lsgd_status lsgd_get_leaders(lsgd_population* pop, int32_t* local_leaders, int32_t* global_leader)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    hipError_t e = hipSuccess;
+    if (local_leaders)
+        e = hipMemcpyAsync(local_leaders, pop->st.lead, sizeof(int32_t) * (size_t)pop->cfg.n_groups, hipMemcpyDeviceToHost, pop->stream);
+    if (e == hipSuccess && global_leader)
+        e = hipMemcpyAsync(global_leader, pop->st.glead, sizeof(int32_t), hipMemcpyDeviceToHost, pop->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "get_leaders: %s", hipGetErrorString(e));
+    return LSGD_OK;
+}
+
+lsgd_status lsgd_get_losses(lsgd_population* pop, float* losses_host)
+{
+    if (!pop || !losses_host) return fail(LSGD_ERR_INVALID_ARG, "population or output is NULL");
+    hipError_t e = hipMemcpyAsync(losses_host, pop->st.losses, sizeof(float) * (size_t)pop->cfg.W, hipMemcpyDeviceToHost, pop->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "get_losses: %s", hipGetErrorString(e));
+    return LSGD_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,77 @@
+// Internal declarations shared by the HIP translation units of liblsgd.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lsgd.h"
+
+namespace lsgd {
+
+constexpr int kWave = 64;
+
+// Device-side bookkeeping placed at the start of the caller's workspace.
+struct DeviceState {
+    int32_t* lead;      // [G]   local leader of each group (-1 = never selected)
+    int32_t* glead;     // [1]   global leader
+    int32_t* refreshed; // [G+1] 1 = leader re-selected since the last update (capture from x)
+    int32_t* offsets;   // [G+1] group j owns rows [offsets[j], offsets[j+1])
+    int32_t* group_of;  // [W]
+    float* losses;      // [W]   the population's own loss buffer
+    float* partials;    // scratch for loss partial sums
+    size_t partials_cap;
+    char* scratch;      // workload scratch (activations, sort buffers ...)
+    size_t scratch_bytes;
+};
+
+struct RefreshBits {
+    uint64_t w[LSGD_MAX_GROUPS / 64];
+};
+
+// ---- kernels' host launchers (each returns the hipError_t of its launches) ----
+hipError_t launch_init_state(const DeviceState& st, int W, int G, hipStream_t s);
+
+hipError_t launch_select_leaders(const float* losses, int W, int G, const DeviceState& st,
+                                 const RefreshBits& bits, const RefreshBits& capture, int refresh_global,
+                                 int capture_global, hipStream_t s);
+
+struct PullParams {
+    float* x;
+    const float* g;
+    float* m;           // may be NULL when mu == 0
+    float* Z;           // may be NULL
+    uint16_t* xb;       // bf16 shadow or NULL
+    int64_t P, ld;
+    int W, G;
+    float eta, lamL, lamG, mu, wd;
+    int flags;          // LSGD_NESTEROV | LSGD_LEADER_EXEMPT | LSGD_MOMENTUM_GRAD_ONLY
+    int use_refreshed;  // 0: treat every leader as kept (read Z)
+    int clear_refreshed;
+};
+hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s);
+
+hipError_t launch_cast_shadow(const float* x, uint16_t* xb, int W, int64_t P, int64_t ld, hipStream_t s);
+
+size_t mc_scratch_bytes(int W, const lsgd_mc_batch& b);
+size_t mc_partials(int W, const lsgd_mc_batch& b);
+hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, int64_t P, int64_t ld,
+                               const lsgd_mc_batch& b, const DeviceState& st, hipStream_t s);
+
+size_t mlp_scratch_bytes(int W, const lsgd_mlp_batch& b);
+// returns LSGD_OK / LSGD_ERR_UNSUPPORTED through *status for shapes the kernels do not cover
+hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, float* losses, int W,
+                                int64_t P, int64_t ld, const lsgd_mlp_batch& b, const DeviceState& st,
+                                hipStream_t s);
+bool mlp_shape_supported(const lsgd_mlp_batch& b, const char** why);
+
+// ---- small device helpers ----
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float v)
+{
+    uint32_t u = __float_as_uint(v);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16) | ((u & 0xFFFFu) ? 0x40u : 0u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+} // namespace lsgd

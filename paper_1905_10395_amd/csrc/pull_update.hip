@@ -1,0 +1,230 @@
+// Fused leader-pull (+ momentum) update of the whole population, one pass.
+//
+//   d   = g + wd*x + lam_L (x - z_local) + lam_G (x - z_global)
+//   mu = 0:  x <- x - eta*d            mu > 0:  m <- mu*m + d ; x <- x - eta*m
+//
+// (arXiv 1905.10395: supplement B.1 for the eta-scaled step, Eq. 3 for the two
+// pulls, Algorithm 1 for leader copies kept between communications.)
+//
+// Geometry.  The update is independent per parameter column, so a workgroup
+// owns a tile of columns for ALL W rows.  It first captures the global
+// leader's tile, then walks the groups; for each group it captures the local
+// leader's tile before touching any row of that group.  A re-selected leader
+// is captured from x itself (and written to the kept-copy buffer Z if there is
+// one); a kept leader is read from Z.  Because the tile's only writer is this
+// workgroup and every capture precedes the stores it could race with, the
+// update is safely in place and the "broadcast" of the leader costs no extra
+// pass over memory.  The kernel is bound by HBM traffic: 20 B per parameter
+// with momentum (read x, g, m; write x, m), 12 B without.
+#include "common.h"
+
+namespace lsgd {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned short v4h __attribute__((ext_vector_type(4)));
+
+template <int VEC> struct Vec;
+template <> struct Vec<4> { using type = v4f; };
+template <> struct Vec<1> { using type = float; };
+
+template <int VEC> __device__ __forceinline__ typename Vec<VEC>::type ld_vec(const float* p);
+template <> __device__ __forceinline__ v4f ld_vec<4>(const float* p) { return *reinterpret_cast<const v4f*>(p); }
+template <> __device__ __forceinline__ float ld_vec<1>(const float* p) { return *p; }
+
+template <int VEC> __device__ __forceinline__ typename Vec<VEC>::type ld_stream(const float* p);
+template <> __device__ __forceinline__ v4f ld_stream<4>(const float* p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+}
+template <> __device__ __forceinline__ float ld_stream<1>(const float* p) { return __builtin_nontemporal_load(p); }
+
+__device__ __forceinline__ void st_vec(float* p, v4f v) { *reinterpret_cast<v4f*>(p) = v; }
+__device__ __forceinline__ void st_vec(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st_stream(float* p, v4f v) { __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p)); }
+__device__ __forceinline__ void st_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
+
+__device__ __forceinline__ void st_bf16(uint16_t* p, v4f v)
+{
+    v4h o = {f32_to_bf16_rne(v.x), f32_to_bf16_rne(v.y), f32_to_bf16_rne(v.z), f32_to_bf16_rne(v.w)};
+    *reinterpret_cast<v4h*>(p) = o;
+}
+__device__ __forceinline__ void st_bf16(uint16_t* p, float v) { *p = f32_to_bf16_rne(v); }
+
+struct Coef {
+    float eta, cL, cG, mu, wd;
+    int nesterov, grad_only;
+};
+
+// One parameter (or four, element-wise).  Written with plain operators so that
+// the compiler forms the fused multiply-adds itself.
+template <bool MOM, class V>
+__device__ __forceinline__ void update_vec(V& x, const V g, V& m, const V zl, const V zg, const Coef& c)
+{
+    V d = g + c.wd * x;
+    const V pull = c.cL * (x - zl) + c.cG * (x - zg);
+    V step;
+    if (MOM) {
+        if (c.grad_only) {
+            m = c.mu * m + d;
+            step = (c.nesterov ? d + c.mu * m : m) + pull;
+        } else {
+            d += pull;
+            m = c.mu * m + d;
+            step = c.nesterov ? d + c.mu * m : m;
+        }
+    } else {
+        step = d + pull;
+    }
+    x = x - c.eta * step;
+}
+
+__device__ __forceinline__ v4f zero_of(v4f) { return (v4f)(0.f); }
+__device__ __forceinline__ float zero_of(float) { return 0.f; }
+
+constexpr int kPullThreads = 256;
+
+struct PullDev {
+    float* x;
+    const float* g;
+    float* m;
+    float* Z;
+    uint16_t* xb;
+    int64_t col0, col1, ld; // columns [col0, col1)
+    int W, G;
+    float eta, lamL, lamG, mu, wd;
+    int flags, use_refreshed;
+    const int32_t* offsets;
+    const int32_t* lead;
+    const int32_t* glead;
+    const int32_t* refreshed;
+};
+
+template <int VEC, bool MOM, int UNROLL>
+__global__ __launch_bounds__(kPullThreads) void pull_update_kernel(PullDev a)
+{
+    using V = typename Vec<VEC>::type;
+    const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
+    if (col >= a.col1) return;
+
+    Coef c;
+    c.eta = a.eta; c.mu = a.mu; c.wd = a.wd;
+    c.nesterov = (a.flags & LSGD_NESTEROV) != 0;
+    c.grad_only = (a.flags & LSGD_MOMENTUM_GRAD_ONLY) != 0;
+    const bool exempt = (a.flags & LSGD_LEADER_EXEMPT) != 0;
+    const bool pullG = a.lamG != 0.0f, pullL = a.lamL != 0.0f;
+
+    V zg = zero_of(V());
+    const int gl = pullG ? a.glead[0] : -1;
+    if (pullG) {
+        const bool fresh = a.use_refreshed && a.refreshed[a.G];
+        const float* src = fresh ? a.x + (int64_t)gl * a.ld : a.Z + (int64_t)a.G * a.ld;
+        zg = ld_vec<VEC>(src + col);
+        if (fresh && a.Z) st_vec(a.Z + (int64_t)a.G * a.ld + col, zg);
+    }
+
+    for (int j = 0; j < a.G; ++j) {
+        const int r0 = a.offsets[j], r1 = a.offsets[j + 1];
+        V zl = zero_of(V());
+        const int ll = pullL ? a.lead[j] : -1;
+        if (pullL) {
+            const bool fresh = a.use_refreshed && a.refreshed[j];
+            const float* src = fresh ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld;
+            zl = ld_vec<VEC>(src + col);
+            if (fresh && a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, zl);
+        }
+        int i = r0;
+        for (; i + UNROLL <= r1; i += UNROLL) {
+            V xv[UNROLL], gv[UNROLL], mv[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int64_t o = (int64_t)(i + u) * a.ld + col;
+                xv[u] = ld_vec<VEC>(a.x + o);
+                gv[u] = ld_stream<VEC>(a.g + o);
+                mv[u] = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
+            }
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                const int64_t o = (int64_t)(i + u) * a.ld + col;
+                c.cL = (exempt && (i + u) == ll) ? 0.0f : a.lamL;
+                c.cG = (exempt && (i + u) == gl) ? 0.0f : a.lamG;
+                update_vec<MOM, V>(xv[u], gv[u], mv[u], zl, zg, c);
+                st_stream(a.x + o, xv[u]);
+                if (MOM) st_stream(a.m + o, mv[u]);
+                if (a.xb) st_bf16(a.xb + o, xv[u]);
+            }
+        }
+        for (; i < r1; ++i) {
+            const int64_t o = (int64_t)i * a.ld + col;
+            V xv = ld_vec<VEC>(a.x + o);
+            V gv = ld_stream<VEC>(a.g + o);
+            V mv = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
+            c.cL = (exempt && i == ll) ? 0.0f : a.lamL;
+            c.cG = (exempt && i == gl) ? 0.0f : a.lamG;
+            update_vec<MOM, V>(xv, gv, mv, zl, zg, c);
+            st_stream(a.x + o, xv);
+            if (MOM) st_stream(a.m + o, mv);
+            if (a.xb) st_bf16(a.xb + o, xv);
+        }
+    }
+}
+
+__global__ void clear_refreshed_kernel(int32_t* refreshed, int G)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t <= G) refreshed[t] = 0;
+}
+
+template <int VEC, bool MOM>
+static void launch_range(PullDev a, hipStream_t s)
+{
+    const int64_t cols = a.col1 - a.col0;
+    if (cols <= 0) return;
+    const int64_t per_block = (int64_t)kPullThreads * VEC;
+    const int64_t blocks = (cols + per_block - 1) / per_block;
+    hipLaunchKernelGGL((pull_update_kernel<VEC, MOM, 4>), dim3((unsigned)blocks), dim3(kPullThreads), 0, s, a);
+}
+
+hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s)
+{
+    PullDev a;
+    a.x = p.x; a.g = p.g; a.m = p.m; a.Z = p.Z; a.xb = p.xb;
+    a.ld = p.ld; a.W = p.W; a.G = p.G;
+    a.eta = p.eta; a.lamL = p.lamL; a.lamG = p.lamG; a.mu = p.mu; a.wd = p.wd;
+    a.flags = p.flags; a.use_refreshed = p.use_refreshed;
+    a.offsets = st.offsets; a.lead = st.lead; a.glead = st.glead; a.refreshed = st.refreshed;
+    const bool mom = p.mu != 0.0f;
+
+    auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    const bool vec_ok = (p.ld % 4 == 0) && aligned16(p.x) && aligned16(p.g) && (!mom || aligned16(p.m)) &&
+                        (!p.Z || aligned16(p.Z)) && (!p.xb || (reinterpret_cast<uintptr_t>(p.xb) & 7u) == 0);
+    const int64_t P4 = vec_ok ? (p.P & ~(int64_t)3) : 0;
+    // whole v4f columns, then the ragged tail (or everything) element-wise
+    a.col0 = 0; a.col1 = P4;
+    if (mom) launch_range<4, true>(a, s); else launch_range<4, false>(a, s);
+    a.col0 = P4; a.col1 = p.P;
+    if (mom) launch_range<1, true>(a, s); else launch_range<1, false>(a, s);
+    if (p.clear_refreshed) {
+        int threads = 256, blocks = (p.G + 1 + threads - 1) / threads;
+        hipLaunchKernelGGL(clear_refreshed_kernel, dim3(blocks), dim3(threads), 0, s, st.refreshed, p.G);
+    }
+    return hipGetLastError();
+}
+
+// ---- whole-matrix fp32 -> bf16 cast (initial fill of the shadow) ----
+__global__ __launch_bounds__(256) void cast_shadow_kernel(const float* __restrict__ x, uint16_t* __restrict__ xb,
+                                                          int64_t P, int64_t ld)
+{
+    const int64_t row = blockIdx.y;
+    for (int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; c < P; c += (int64_t)gridDim.x * blockDim.x)
+        xb[row * ld + c] = f32_to_bf16_rne(x[row * ld + c]);
+}
+
+hipError_t launch_cast_shadow(const float* x, uint16_t* xb, int W, int64_t P, int64_t ld, hipStream_t s)
+{
+    int64_t blocks = (P + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(cast_shadow_kernel, dim3((unsigned)blocks, (unsigned)W), dim3(256), 0, s, x, xb, P, ld);
+    return hipGetLastError();
+}
+
+} // namespace lsgd

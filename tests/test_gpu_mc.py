@@ -1,0 +1,108 @@
+"""GPU parity: matrix-completion gradients and whole LSGD steps against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_1905_10395_amd as L
+from gpu_util import DEV, Pair, dev, rel_l2_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def mc_batch(prob, idx_dev, c):
+    return L.MCBatch(prob.m, prob.n, prob.r, prob._rows_d, prob._cols_d, prob._vals_d, idx_dev, c)
+
+
+def upload(prob):
+    prob._rows_d, prob._cols_d, prob._vals_d = dev(prob.rows), dev(prob.cols), dev(prob.vals)
+    return prob
+
+
+@pytest.mark.parametrize("m,n,r,frac,W,B", [
+    (100, 100, 5, 0.30, 4, None),          # full-batch tiny config
+    (300, 200, 32, 0.10, 3, 5000),         # rank-32 rows, duplicates in the batch
+    (257, 129, 7, 0.20, 2, 1111),          # odd rank, ragged everything
+    (50, 60, 64, 0.50, 2, 700),
+    (40, 30, 100, 0.50, 2, 300),           # rank above a wavefront
+    (64, 64, 1, 0.50, 2, 100),
+])
+def test_mc_grad_loss_matches_oracle(m, n, r, frac, W, B):
+    prob = upload(wl.mc_problem(m, n, r, frac, 1.0, noise_std=0.01, seed=m + r))
+    ld = wl.padded_ld(prob.P, 4)
+    x0 = wl.mc_init(W, prob, 0.7, ld=ld, seed=r)
+    idx = None if B is None else wl.mc_batches(W, B, prob.n_obs, 1, seed=m)[0]
+    c = 0.5 if B is None else 0.5 * prob.n_obs / B
+    idx_d = None if idx is None else dev(idx)
+    batch = mc_batch(prob, idx_d, c)
+    pr = Pair(x0, np.array([0, W], dtype=np.int32), P=prob.P, largest_batch=batch)
+    pr.g.fill_(123.0)                       # stale contents must be overwritten, padding zeroed
+    pr.ora.grad_loss_mc(m, n, r, prob.rows, prob.cols, prob.vals, idx, c)
+    pr.pop.grad_loss(batch)
+    torch.cuda.synchronize()
+    g = pr.g.cpu().numpy()
+    assert rel_l2_rows(g[:, :prob.P], pr.ora.g[:, :prob.P]).max() < 1e-5
+    assert np.all(g[:, prob.P:] == 0)
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-5)
+
+
+def test_mc_empty_batch_gives_zero():
+    prob = upload(wl.mc_problem(20, 20, 4, 0.5, 1.0, seed=2))
+    x0 = wl.mc_init(2, prob, 1.0, seed=2)
+    idx_d = torch.zeros((2, 0), dtype=torch.int32, device=DEV)
+    batch = mc_batch(prob, idx_d, 1.0)
+    pr = Pair(x0, np.array([0, 2], dtype=np.int32), largest_batch=batch)
+    pr.g.fill_(5.0)
+    pr.pop.grad_loss(batch)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(pr.g) == 0 and pr.pop.get_losses() == [0.0, 0.0]
+
+
+def test_tiny_lgd_config_200_steps():
+    """100x100 rank 5, 30% observed, 4 workers in one group, full-batch gradient, eta 0.01,
+    lam_L 0.1, lam_G 0, leaders refreshed every step, 200 steps; leader indices exact (near-tie
+    protocol), state within 1e-4 after one step and 1e-3 after 100 and 200."""
+    prob = upload(wl.mc_problem(100, 100, 5, 0.30, 1.0, seed=11))
+    W = 4
+    x0 = wl.mc_init(W, prob, 1.0, seed=11)
+    batch = mc_batch(prob, None, 0.5)
+    pr = Pair(x0, np.array([0, W], dtype=np.int32), snapshot=False, largest_batch=batch)
+    flips = 0
+    for t in range(200):
+        pr.ora.grad_loss_mc(prob.m, prob.n, prob.r, prob.rows, prob.cols, prob.vals, None, 0.5)
+        pr.ora.select(); pr.ora.update(0.01, 0.1, 0.0)
+        pr.pop.step(batch, 0.01, 0.1, 0.0)
+        if t in (0, 99, 199):
+            np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4 if t == 0 else 1e-3)
+            pr.check_state(1e-4 if t == 0 else 1e-3, f"step {t}")
+        if not pr.check_leaders():
+            flips += 1; pr.resync_from_oracle()
+    assert flips <= 2
+    # and the problem is solved (losses fell by > 1000x)
+    assert min(pr.pop.get_losses()) < 1e-3 * 3000
+
+
+def test_lsgd_steps_minibatch_groups_stale_leaders():
+    """Scaled-down multi-leader config: 16 workers in 4 groups, sampled batches, leaders
+    refreshed every 4 steps, eta 0.005, lam_L 0.1, lam_G 0.05."""
+    prob = upload(wl.mc_problem(600, 500, 32, 0.05, 32 ** -0.5, noise_std=0.01, seed=21))
+    W, G, B, steps = 16, 4, 2048, 24
+    ld = wl.padded_ld(prob.P)
+    x0 = wl.mc_init(W, prob, 32 ** -0.5, ld=ld, seed=21)
+    idx = wl.mc_batches(W, B, prob.n_obs, steps, seed=21)
+    idx_d = dev(idx)
+    c = 0.5 * prob.n_obs / B
+    b0 = mc_batch(prob, idx_d[0], c)
+    pr = Pair(x0, wl.equal_group_offsets(W, G), P=prob.P, largest_batch=b0)
+    for t in range(steps):
+        rl, rg = wl.refresh_masks(t, 4, G)
+        pr.ora.grad_loss_mc(prob.m, prob.n, prob.r, prob.rows, prob.cols, prob.vals, idx[t], c)
+        pr.ora.select(rl, rg); pr.ora.update(0.005, 0.1, 0.05, rl, rg)
+        pr.pop.step(mc_batch(prob, idx_d[t], c), 0.005, 0.1, 0.05, rl, rg)
+        if not pr.check_leaders(rl, rg):
+            pr.resync_from_oracle()
+        if t == 0:
+            pr.check_state(1e-4, "step 0")
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-3)
+    pr.check_state(1e-3, f"after {steps} steps")

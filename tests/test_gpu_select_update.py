@@ -1,0 +1,177 @@
+"""GPU parity: leader selection and the fused pull update against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_1905_10395_amd as L
+from gpu_util import DEV, Pair, dev, rel_l2_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def random_offsets(r, W, G):
+    cuts = np.sort(r.choice(np.arange(1, W), size=G - 1, replace=False)) if G > 1 else np.array([], dtype=int)
+    return np.concatenate([[0], cuts, [W]]).astype(np.int32)
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("W,G", [(1, 1), (4, 1), (16, 4), (32, 4), (64, 7), (63, 5), (65, 3), (200, 9), (1000, 64)])
+def test_select_leaders_bit_exact(W, G):
+    r = wl.stream("gpu_sel", W, G)
+    off = random_offsets(r, W, G)
+    x0 = np.zeros((W, 8), dtype=np.float32)
+    pr = Pair(x0, off)
+    pool = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.0, 1.0, -2.5], dtype=np.float32)
+    for trial in range(12):
+        losses = r.standard_normal(W).astype(np.float32)
+        if trial % 3 == 1:
+            k = int(r.integers(1, W + 1)); pos = r.choice(W, size=k, replace=False)
+            losses[pos] = pool[r.integers(0, len(pool), size=k)]
+        if trial % 3 == 2:
+            losses[:] = np.float32(r.choice(pool))          # everything tied (or all NaN / inf)
+        rl = (r.random(G) < 0.6).astype(np.uint8) if trial % 2 else None
+        rg = int(trial % 4 != 3)
+        if trial == 0:
+            rl, rg = None, 1
+        pr.ora.losses[:] = losses
+        pr.ora.select(rl, rg)
+        pr.pop.select_leaders(dev(losses), rl, rg)
+        lead, gl = pr.pop.get_leaders()
+        assert lead == pr.ora.lead.tolist(), (trial, losses, off)
+        assert gl == int(pr.ora.glead[0])
+
+
+# ---------------------------------------------------------------------------
+CASES = [
+    # W, G, P, ld, mu, flags, wd
+    (4, 1, 1000, 1000, 0.0, 0, 0.0),
+    (16, 4, 4099, 4160, 0.9, 0, 0.0),                       # ragged P, padded rows
+    (32, 4, 70001, 70004, 0.9, L.NESTEROV, 1e-4),
+    (8, 2, 5000, 5001, 0.9, 0, 0.0),                        # ld % 4 != 0: scalar path
+    (7, 3, 3003, 3004, 0.5, L.MOMENTUM_GRAD_ONLY, 0.0),     # unequal groups
+    (7, 3, 3003, 3004, 0.5, L.MOMENTUM_GRAD_ONLY | L.NESTEROV, 1e-3),
+    (12, 3, 2048, 2048, 0.0, L.PULL_UNSCALED_BY_ETA, 0.0),
+    (12, 3, 2050, 2052, 0.9, L.LEADER_EXEMPT, 0.0),
+    (5, 5, 515, 516, 0.9, 0, 0.0),                          # every worker its own group
+    (70, 6, 1030, 1032, 0.9, 0, 0.0),                       # W > 64
+]
+
+
+@pytest.mark.parametrize("W,G,P,ld,mu,flags,wd", CASES)
+def test_pull_update_one_step_and_stale_periods(W, G, P, ld, mu, flags, wd):
+    r = wl.stream("gpu_pull", W, G, P)
+    off = random_offsets(r, W, G) if W % G else wl.equal_group_offsets(W, G)
+    x0, g0, _ = wl.stress_state(W, P, ld, seed=W * 1000 + G)
+    pr = Pair(x0, off, P=P, momentum=mu, flags=flags, weight_decay=wd)
+    eta, lamL, lamG = 0.05, 0.1, 0.05
+    tau = 3
+    for t in range(7):
+        g = wl.stress_grad(W, P, ld, t, seed=W)
+        losses = wl.stress_losses(W, t, seed=W + G)
+        pr.set_grad(g, losses)
+        rl, rg = wl.refresh_masks(t, tau, G, staggered=(G > 1), tau_G=2 * tau)
+        pr.ora.select(rl, rg); pr.ora.update(eta, lamL, lamG, rl, rg)
+        pr.pop.select_leaders(pr.losses_dev, rl, rg)
+        pr.pop.pull_update(eta, lamL, lamG)
+        assert pr.check_leaders(rl, rg)
+        pr.check_state(1e-4 if t == 0 else 3e-4, f"step {t}")
+        # kept leader copies are the oracle's, bit for bit (pure copies)
+        np.testing.assert_array_equal(pr.Z.cpu().numpy()[:, :P], pr.ora.Z[:, :P])
+    # padding columns are never touched
+    if ld > P:
+        assert np.array_equal(pr.x.cpu().numpy()[:, P:], x0[:, P:])
+
+
+def test_in_place_equals_out_of_place_bitwise():
+    """The leader rows are read by every other row's update while being updated themselves:
+    capturing them first must make the in-place result identical to one computed from copies."""
+    W, G, P = 16, 4, 9001
+    ld = wl.padded_ld(P, 4)
+    x0, g0, _ = wl.stress_state(W, P, ld, seed=3)
+    losses = wl.stress_losses(W, 0, seed=3)
+    off = wl.equal_group_offsets(W, G)
+    a = Pair(x0, off, P=P, momentum=0.9)
+    a.set_grad(g0, losses)
+    a.pop.select_leaders(a.losses_dev); a.pop.pull_update(0.1, 0.3, 0.2)
+    lead, gl = a.pop.get_leaders()
+    # second population: same inputs, but leaders supplied as kept copies (no aliasing with x)
+    b = Pair(x0, off, P=P, momentum=0.9)
+    b.set_grad(g0, losses)
+    b.pop.select_leaders(b.losses_dev); b.pop.pull_update(0.0, 0.0, 0.0)     # consumes the refresh, moves nothing
+    b.m.zero_()
+    Z = np.concatenate([x0[lead], x0[[gl]]]); b.Z.copy_(dev(Z))
+    with pytest.raises(L.LsgdError):           # copies were never captured (coefficients were zero)
+        b.pop.pull_update(0.1, 0.3, 0.2)
+    c = Pair(x0, off, P=P, momentum=0.9)
+    c.set_grad(g0, losses)
+    c.pop.select_leaders(c.losses_dev); c.pop.pull_update(0.0, 1e-30, 1e-30)  # captures copies, moves nothing
+    c.x.copy_(dev(x0)); c.m.zero_()
+    c.pop.pull_update(0.1, 0.3, 0.2)
+    torch.cuda.synchronize()
+    assert torch.equal(a.x, c.x) and torch.equal(a.m, c.m)
+
+
+def test_state_errors_and_no_side_effects():
+    W, P = 4, 64
+    x0, g0, _ = wl.stress_state(W, P, P, seed=1)
+    pr = Pair(x0, wl.equal_group_offsets(W, 2), P=P, snapshot=False)
+    with pytest.raises(L.LsgdError, match="STATE"):
+        pr.pop.pull_update(0.1, 0.1, 0.0)                  # nothing selected yet
+    pr.set_grad(g0, wl.stress_losses(W, 0))
+    pr.pop.select_leaders(pr.losses_dev)
+    pr.pop.pull_update(0.1, 0.1, 0.1)                      # fine: full refresh, no kept copies needed
+    with pytest.raises(L.LsgdError, match="z_snapshot"):
+        pr.pop.pull_update(0.1, 0.1, 0.1)                  # stale step without a snapshot buffer
+    with pytest.raises(L.LsgdError, match="finite"):
+        pr.pop.pull_update(float("nan"), 0.1, 0.1)
+    before = pr.x.clone()
+    with pytest.raises(L.LsgdError):
+        pr.pop.step(L.ExternalBatch(pr.losses_dev), 0.1, 0.1, 0.1, [0, 0], 0)
+    torch.cuda.synchronize()
+    assert torch.equal(before, pr.x)
+    pr.pop.pull_update(0.1, 0.0, 0.0)                      # zero pulls never need leaders
+
+
+def test_zero_pulls_is_sgd_on_gpu():
+    W, P = 6, 777
+    ld = 780
+    x0, g0, _ = wl.stress_state(W, P, ld, seed=5)
+    pr = Pair(x0, wl.equal_group_offsets(W, 3), P=P, momentum=0.9, flags=L.NESTEROV, snapshot=False)
+    tx = torch.tensor(x0[:, :P], dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([tx], lr=0.05, momentum=0.9, nesterov=True)
+    for t in range(3):
+        g = wl.stress_grad(W, P, ld, t, seed=5)
+        pr.set_grad(g, wl.stress_losses(W, t))
+        pr.pop.pull_update(0.05, 0.0, 0.0)
+        tx.grad = torch.tensor(g[:, :P], dtype=torch.float64); opt.step()
+    torch.cuda.synchronize()
+    assert rel_l2_rows(pr.x.cpu().numpy()[:, :P], tx.detach().numpy()).max() < 1e-6
+
+
+def test_hundred_steps_external_quadratic():
+    """100 fp32 steps with leader flips: diagonal quadratic, gradient computed on the host from
+    the GPU's own iterates would hide drift, so both sides get the gradient of their own state."""
+    W, G, P = 8, 2, 4096
+    r = wl.stream("gpu_quad")
+    A = np.linspace(0.5, 4.0, P).astype(np.float32)
+    x0 = (r.standard_normal((W, P)) * 2).astype(np.float32)
+    pr = Pair(x0, wl.equal_group_offsets(W, G), momentum=0.9)
+    Ad = dev(A)
+    flips = 0
+    for t in range(100):
+        # oracle side
+        xo = pr.ora.x.astype(np.float64)
+        pr.ora.g[:] = (A * xo).astype(np.float32)
+        pr.ora.losses[:] = (0.5 * np.sum(A * xo * xo, axis=1)).astype(np.float32)
+        # GPU side: gradient of its own state (torch elementwise, caller-supplied gradient)
+        pr.g.copy_(Ad * pr.x)
+        losses_dev = (0.5 * (Ad.double() * pr.x.double() * pr.x.double()).sum(1)).float()
+        rl, rg = wl.refresh_masks(t, 4, G)
+        pr.ora.select(rl, rg); pr.ora.update(0.05, 0.1, 0.05, rl, rg)
+        pr.pop.select_leaders(losses_dev, rl, rg); pr.pop.pull_update(0.05, 0.1, 0.05)
+        if not pr.check_leaders(rl, rg):
+            flips += 1; pr.resync_from_oracle()
+    pr.check_state(1e-3, "after 100 steps")
+    assert flips <= 2
