@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Throughput of the batched LSGD step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c4]
+
+Prints ONE JSON line.  `value` is worker-steps/s (W workers x steps / seconds)
+of the whole step with every input already resident in HBM.  `roofline`
+describes the dominant kernel of the workload, timed live with events on the
+stream the library launches on; `cpu_baseline` is the CPU oracle timed on a
+bounded sample of the same workload on this host.  The line also carries the
+pull-update bandwidth stress (`pull_update_stress`) whichever workload is the
+primary one, because the metric names both quantities.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+import workloads as wl
+
+METRIC = "worker-steps/sec and pull-update HBM GB/s (% of peak) at W workers, 1 MI355X"
+HBM_PEAK_GBS = 8000.0
+DEV = "cuda:0"
+
+
+def _events_ms(fn, reps):
+    """Average milliseconds per call of fn over `reps` back-to-back calls (events on the current stream)."""
+    a = torch.cuda.Event(enable_timing=True)
+    b = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(reps):
+        fn(i)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def _timed_steps(step_fn, steps, warmup):
+    for t in range(warmup):
+        step_fn(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        step_fn(warmup + t)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0)
+
+
+# ------------------------------------------------------------------------------------------
+# C4: pull-update bandwidth stress (leader selection + fused pull/momentum update only)
+# ------------------------------------------------------------------------------------------
+def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512):
+    ld = wl.padded_ld(P)
+    gen = torch.Generator(device=DEV); gen.manual_seed(wl.MASTER_SEED)
+    x = torch.randn((W, ld), device=DEV, generator=gen) * 0.05
+    g = torch.randn((W, ld), device=DEV, generator=gen) * 1e-2
+    m = torch.zeros((W, ld), device=DEV)
+    losses = torch.rand((16, W), device=DEV, generator=gen)
+    batches = [L.ExternalBatch(losses[i]) for i in range(16)]
+    pop = L.Population(x, g, G, m=m, P=P, momentum=0.9)
+    eta, lamL, lamG = 0.01, 0.1, 0.05
+
+    def step(t):
+        pop.step(batches[t % 16], eta, lamL, lamG)
+
+    secs = _timed_steps(step, steps, warmup)
+    # the update kernel alone (select once, then updates from the same leaders need kept copies;
+    # a full refresh per call keeps it the same launch the step makes)
+    def upd(i):
+        pop.select_leaders(losses[i % 16]); pop.pull_update(eta, lamL, lamG)
+    def sel(i):
+        pop.select_leaders(losses[i % 16])
+    ms_both = _events_ms(upd, max(steps, 10))
+    ms_sel = _events_ms(sel, 200)
+    ms_pull = ms_both - ms_sel
+    bytes_per_launch = 20.0 * W * P
+    ach = bytes_per_launch / (ms_pull * 1e-3) / 1e9
+    out = {
+        "workload": f"pull-update stress: W={W} x P={P} fp32 in {G} groups, momentum 0.9, select+pull only",
+        "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
+        "roofline": {"kernel": "pull_update_kernel<4,true,4>", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": bytes_per_launch, "ms_per_launch": ms_pull},
+        "ms_select": ms_sel,
+    }
+    del pop, x, g, m
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_stress(W=32, G=4, P=11_689_512, frac=8):
+    """Oracle select + update on the first P/frac columns of the same population shape."""
+    import oracle
+    Ps = P // frac
+    x0, g0, _ = wl.stress_state(W, Ps, Ps)
+    pop = oracle.Population(x0, wl.equal_group_offsets(W, G), momentum=0.9)
+    pop.g[:] = g0
+    reps, t0 = 0, time.perf_counter()
+    while reps < 3 or time.perf_counter() - t0 < 8.0:
+        pop.losses[:] = wl.stress_losses(W, reps)
+        pop.select(); pop.update(0.01, 0.1, 0.05)
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": W / (dt * frac), "unit": "worker-steps/s", "cores": os.cpu_count() if _omp_threads() is None else _omp_threads(),
+            "kind": "oracle", "sample": f"all {W} workers, first 1/{frac} of the columns ({Ps}), {reps} steps; "
+            f"time scaled by {frac} (the update is independent per column)"}
+
+
+def _omp_threads():
+    v = os.environ.get("OMP_NUM_THREADS")
+    return int(v) if v and v.isdigit() else None
+
+
+# ------------------------------------------------------------------------------------------
+# C2: matrix-completion LSGD (whole step: gradients+losses -> leaders -> pull update)
+# ------------------------------------------------------------------------------------------
+def make_c2():
+    prob = wl.mc_problem(20000, 20000, 32, 0.01, 32 ** -0.5, noise_std=0.01)
+    W, G, B, K = 16, 4, 65536, 16
+    ld = wl.padded_ld(prob.P)
+    x0 = wl.mc_init(W, prob, 32 ** -0.5, ld=ld)
+    idx = wl.mc_batches(W, B, prob.n_obs, K)
+    return prob, W, G, B, K, ld, x0, idx
+
+
+def run_c2(L, steps, warmup, data):
+    prob, W, G, B, K, ld, x0, idx = data
+    d = lambda a: torch.from_numpy(a).to(DEV)
+    x = d(x0); g = torch.zeros_like(x)
+    Z = torch.zeros((G + 1, ld), device=DEV)
+    rows, cols, vals, idx_d = d(prob.rows), d(prob.cols), d(prob.vals), d(idx)
+    c = 0.5 * prob.n_obs / B
+    batches = [L.MCBatch(prob.m, prob.n, prob.r, rows, cols, vals, idx_d[k], c) for k in range(K)]
+    pop = L.Population(x, g, G, z_snapshot=Z, P=prob.P, largest_batch=batches[0])
+    eta, lamL, lamG, tau = 0.005, 0.1, 0.05, 4
+
+    def step(t):
+        rl, rg = wl.refresh_masks(t, tau, G)
+        pop.step(batches[t % K], eta, lamL, lamG, rl, rg)
+
+    secs = _timed_steps(step, steps, warmup)
+    reps = max(20, min(steps, 200))
+    ms_grad = _events_ms(lambda i: pop.grad_loss(batches[i % K]), reps)
+    ms_sel = _events_ms(lambda i: pop.select_leaders(), reps)
+
+    def upd(i):
+        pop.select_leaders(); pop.pull_update(eta, lamL, lamG)
+    ms_pull = _events_ms(upd, reps) - ms_sel
+    # algorithmic bytes of the gradient stage per launch: read x and write g once (2*4P per worker)
+    # plus 16 B of index + entry per batch element
+    grad_bytes = W * (2 * 4.0 * prob.P + 16.0 * B)
+    ach = grad_bytes / (ms_grad * 1e-3) / 1e9
+    lossv = pop.get_losses()
+    out = {
+        "workload": f"matrix completion LSGD: 20000x20000 rank 32, 1% observed ({prob.n_obs}), W={W} in {G} groups, "
+                    f"B={B}/worker/step, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps",
+        "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
+        "roofline": {"kernel": "lsgd_grad_loss (matrix completion)", "bound": "hbm", "achieved": ach,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": grad_bytes, "ms_per_launch": ms_grad},
+        "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
+        "pull_update_GBs": W * 12.0 * prob.P / (ms_pull * 1e-3) / 1e9,
+        "final_mean_loss": float(np.mean(lossv)),
+    }
+    del pop
+    return out
+
+
+def cpu_c2(data):
+    import oracle
+    prob, W, G, B, K, ld, x0, idx = data
+    pop = oracle.Population(x0, wl.equal_group_offsets(W, G), P=prob.P)
+    c = 0.5 * prob.n_obs / B
+    reps, t0 = 0, time.perf_counter()
+    while reps < 3 or time.perf_counter() - t0 < 8.0:
+        rl, rg = wl.refresh_masks(reps, 4, G)
+        pop.grad_loss_mc(prob.m, prob.n, prob.r, prob.rows, prob.cols, prob.vals, idx[reps % K], c)
+        pop.select(rl, rg); pop.update(0.005, 0.1, 0.05, rl, rg)
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": W / dt, "unit": "worker-steps/s", "cores": _omp_threads() or os.cpu_count(), "kind": "oracle",
+            "sample": f"the full workload (all {W} workers, B={B}), {reps} whole steps"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c4"])
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; every population lives on a single device "
+              "(no collectives, no sharding). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    import paper_1905_10395_amd as L
+    L.lib()
+
+    stress = run_stress(L, min(args.steps, 100), min(args.warmup, 10))
+    line = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
+    if args.workload == "c4":
+        primary = stress
+        cpu = None if args.no_cpu else cpu_stress()
+    else:
+        data = make_c2()
+        primary = run_c2(L, args.steps, args.warmup, data)
+        cpu = None if args.no_cpu else cpu_c2(data)
+    line.update({"value": primary["value"], "unit": primary["unit"], "ms_per_step": primary["ms_per_step"],
+                 "config": {"workload": primary["workload"]}, "roofline": primary["roofline"],
+                 "cpu_baseline": cpu})
+    for k in ("stage_ms", "pull_update_GBs", "final_mean_loss", "ms_select"):
+        if k in primary:
+            line[k] = primary[k]
+    line["pull_update_stress"] = {k: stress[k] for k in ("workload", "value", "unit", "ms_per_step", "roofline")}
+    if args.workload == "c4":
+        line["steps"] = min(args.steps, 100); line["warmup"] = min(args.warmup, 10)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

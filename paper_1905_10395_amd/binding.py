@@ -108,10 +108,16 @@ class MCBatch:
     """rows, cols: int32 [n_obs]; vals: float32 [n_obs]; batch_idx: int32 [W,B] or None (all entries)."""
 
     def __init__(self, m, n, r, rows, cols, vals, batch_idx, c):
-        self.keep = (rows, cols, vals, batch_idx)
         B = 0 if batch_idx is None else int(batch_idx.shape[-1])
+        idx_ptr = None
+        if batch_idx is not None:
+            # an empty tensor has a NULL data pointer, which the C side reads as "all entries"
+            anchor = batch_idx if batch_idx.numel() else torch.zeros(1, dtype=torch.int32, device=rows.device)
+            idx_ptr = anchor.data_ptr()
+            batch_idx = anchor
+        self.keep = (rows, cols, vals, batch_idx)
         self._d = _MC(m, n, r, rows.data_ptr(), cols.data_ptr(), vals.data_ptr(), int(rows.numel()),
-                      None if batch_idx is None else batch_idx.data_ptr(), B, float(c))
+                      idx_ptr, B, float(c))
         self.c = _Batch(BATCH_MC, C.cast(C.pointer(self._d), C.c_void_p))
 
 

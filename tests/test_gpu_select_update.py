@@ -77,8 +77,11 @@ def test_pull_update_one_step_and_stale_periods(W, G, P, ld, mu, flags, wd):
         pr.pop.pull_update(eta, lamL, lamG)
         assert pr.check_leaders(rl, rg)
         pr.check_state(1e-4 if t == 0 else 3e-4, f"step {t}")
-        # kept leader copies are the oracle's, bit for bit (pure copies)
-        np.testing.assert_array_equal(pr.Z.cpu().numpy()[:, :P], pr.ora.Z[:, :P])
+        # kept leader copies are pure copies of rows: bit-exact while the states are (step 0)
+        if t == 0:
+            np.testing.assert_array_equal(pr.Z.cpu().numpy()[:, :P], pr.ora.Z[:, :P])
+        else:
+            assert rel_l2_rows(pr.Z.cpu().numpy()[:, :P], pr.ora.Z[:, :P]).max() < 3e-4
     # padding columns are never touched
     if ld > P:
         assert np.array_equal(pr.x.cpu().numpy()[:, P:], x0[:, P:])
