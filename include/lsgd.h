@@ -59,7 +59,7 @@ enum {
     LSGD_WRITE_BF16_SHADOW = 16   /* pull_update also writes bf16(x) to x_bf16 (MLP operands)     */
 };
 
-#define LSGD_MAX_WORKERS 65536
+#define LSGD_MAX_WORKERS 32768
 #define LSGD_MAX_GROUPS 1024
 
 typedef struct {

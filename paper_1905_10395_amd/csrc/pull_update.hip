@@ -6,16 +6,20 @@
 // (arXiv 1905.10395: supplement B.1 for the eta-scaled step, Eq. 3 for the two
 // pulls, Algorithm 1 for leader copies kept between communications.)
 //
-// Geometry.  The update is independent per parameter column, so a workgroup
-// owns a tile of columns for ALL W rows.  It first captures the global
-// leader's tile, then walks the groups; for each group it captures the local
-// leader's tile before touching any row of that group.  A re-selected leader
-// is captured from x itself (and written to the kept-copy buffer Z if there is
-// one); a kept leader is read from Z.  Because the tile's only writer is this
-// workgroup and every capture precedes the stores it could race with, the
-// update is safely in place and the "broadcast" of the leader costs no extra
-// pass over memory.  The kernel is bound by HBM traffic: 20 B per parameter
-// with momentum (read x, g, m; write x, m), 12 B without.
+// Geometry.  The update is independent per parameter column and bound by HBM
+// traffic: 20 B per parameter with momentum (read x, g, m; write x, m), 12 B
+// without.  It runs in place.  The only rows another row ever reads are the
+// leaders, so the work is split in two launches:
+//   1. pull_rows_kernel streams every row that is not being captured as a
+//      leader, in plain row-major order (sequential x, g, m streams); it
+//      reads the leader tiles it needs from x (leaders re-selected since the
+//      last update, which this launch never writes) or from the kept-copy
+//      buffer Z (Algorithm 1's stored leaders).
+//   2. pull_leaders_kernel then updates the captured leader rows; there a
+//      workgroup owns a column tile for all of them and takes its copies
+//      before it stores anything, and writes the copies to Z.
+// A re-selected leader therefore costs no extra pass over memory: the
+// "broadcast" of the paper is two rows that stay in the memory-side cache.
 #include "common.h"
 
 namespace lsgd {
@@ -94,94 +98,127 @@ struct PullDev {
     float eta, lamL, lamG, mu, wd;
     int flags, use_refreshed;
     const int32_t* offsets;
+    const int32_t* group_of;
     const int32_t* lead;
     const int32_t* glead;
     const int32_t* refreshed;
 };
 
-template <int VEC, bool MOM, int UNROLL>
-__global__ __launch_bounds__(kPullThreads) void pull_update_kernel(PullDev a)
+template <class V>
+__device__ __forceinline__ Coef make_coef(const PullDev& a)
+{
+    Coef c;
+    c.eta = a.eta; c.mu = a.mu; c.wd = a.wd; c.cL = a.lamL; c.cG = a.lamG;
+    c.nesterov = (a.flags & LSGD_NESTEROV) != 0;
+    c.grad_only = (a.flags & LSGD_MOMENTUM_GRAD_ONLY) != 0;
+    return c;
+}
+
+template <int VEC, bool MOM>
+__device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename Vec<VEC>::type xv,
+                                           const typename Vec<VEC>::type zl, const typename Vec<VEC>::type zg, const Coef& c)
+{
+    using V = typename Vec<VEC>::type;
+    V gv = ld_stream<VEC>(a.g + o);
+    V mv = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
+    update_vec<MOM, V>(xv, gv, mv, zl, zg, c);
+    st_stream(a.x + o, xv);
+    if (MOM) st_stream(a.m + o, mv);
+    if (a.xb) st_bf16(a.xb + o, xv);
+}
+
+// Kernel 1: every row that nobody reads as a freshly selected leader.  One
+// workgroup per (row, column tile); the grid's x index runs over the tiles
+// of one row, so workgroups are dispatched in plain row-major order and the
+// x, g, m streams stay sequential in memory.  The leader tiles a row needs
+// (its group's and the global one) are re-read by every row of the group;
+// they are two rows at a time and stay in the memory-side cache.
+template <int VEC, bool MOM>
+__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a)
+{
+    using V = typename Vec<VEC>::type;
+    const int row = blockIdx.y;
+    const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
+    if (col >= a.col1) return;
+    const bool pullG = a.lamG != 0.0f, pullL = a.lamL != 0.0f;
+    const int j = a.group_of[row];
+    const int ll = pullL ? a.lead[j] : -1;
+    const int gl = pullG ? a.glead[0] : -1;
+    const bool freshL = pullL && a.use_refreshed && a.refreshed[j];
+    const bool freshG = pullG && a.use_refreshed && a.refreshed[a.G];
+    // rows captured as leaders in this update are handled by pull_leaders_kernel afterwards
+    if ((freshL && row == ll) || (freshG && row == gl)) return;
+
+    const int64_t o = (int64_t)row * a.ld + col;
+    V xv = ld_stream<VEC>(a.x + o);
+    V zl = zero_of(V()), zg = zero_of(V());
+    if (pullL) zl = ld_vec<VEC>((freshL ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
+    if (pullG) zg = ld_vec<VEC>((freshG ? a.x + (int64_t)gl * a.ld : a.Z + (int64_t)a.G * a.ld) + col);
+    Coef c = make_coef<V>(a);
+    if (a.flags & LSGD_LEADER_EXEMPT) {
+        if (row == ll) c.cL = 0.0f;
+        if (row == gl) c.cG = 0.0f;
+    }
+    update_row<VEC, MOM>(a, o, xv, zl, zg, c);
+}
+
+// Kernel 2 (runs after kernel 1): the rows that were captured as leaders.  A
+// workgroup owns a column tile for all of them, so it can take every copy it
+// needs before it stores anything: first the global leader's tile, whose own
+// row is updated at once (its local pull still sees its group's leader
+// untouched), then each re-selected local leader, whose pull to itself is
+// exactly zero.  Captured tiles are also written to the kept-copy buffer Z.
+template <int VEC, bool MOM>
+__global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
 {
     using V = typename Vec<VEC>::type;
     const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
     if (col >= a.col1) return;
-
-    Coef c;
-    c.eta = a.eta; c.mu = a.mu; c.wd = a.wd;
-    c.nesterov = (a.flags & LSGD_NESTEROV) != 0;
-    c.grad_only = (a.flags & LSGD_MOMENTUM_GRAD_ONLY) != 0;
-    const bool exempt = (a.flags & LSGD_LEADER_EXEMPT) != 0;
     const bool pullG = a.lamG != 0.0f, pullL = a.lamL != 0.0f;
+    const bool exempt = (a.flags & LSGD_LEADER_EXEMPT) != 0;
+    const bool freshG = pullG && a.refreshed[a.G];
+    const int gl = pullG ? a.glead[0] : -1;
+    Coef c = make_coef<V>(a);
 
     V zg = zero_of(V());
-    const int gl = pullG ? a.glead[0] : -1;
-    if (pullG) {
-        const bool fresh = a.use_refreshed && a.refreshed[a.G];
-        const float* src = fresh ? a.x + (int64_t)gl * a.ld : a.Z + (int64_t)a.G * a.ld;
-        zg = ld_vec<VEC>(src + col);
-        if (fresh && a.Z) st_vec(a.Z + (int64_t)a.G * a.ld + col, zg);
-    }
-
-    for (int j = 0; j < a.G; ++j) {
-        const int r0 = a.offsets[j], r1 = a.offsets[j + 1];
-        V zl = zero_of(V());
+    if (pullG) zg = ld_vec<VEC>((freshG ? a.x + (int64_t)gl * a.ld : a.Z + (int64_t)a.G * a.ld) + col);
+    if (freshG) {
+        if (a.Z) st_vec(a.Z + (int64_t)a.G * a.ld + col, zg);
+        const int j = a.group_of[gl];
         const int ll = pullL ? a.lead[j] : -1;
-        if (pullL) {
-            const bool fresh = a.use_refreshed && a.refreshed[j];
-            const float* src = fresh ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld;
-            zl = ld_vec<VEC>(src + col);
-            if (fresh && a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, zl);
-        }
-        int i = r0;
-        for (; i + UNROLL <= r1; i += UNROLL) {
-            V xv[UNROLL], gv[UNROLL], mv[UNROLL];
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const int64_t o = (int64_t)(i + u) * a.ld + col;
-                xv[u] = ld_vec<VEC>(a.x + o);
-                gv[u] = ld_stream<VEC>(a.g + o);
-                mv[u] = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
-            }
-#pragma unroll
-            for (int u = 0; u < UNROLL; ++u) {
-                const int64_t o = (int64_t)(i + u) * a.ld + col;
-                c.cL = (exempt && (i + u) == ll) ? 0.0f : a.lamL;
-                c.cG = (exempt && (i + u) == gl) ? 0.0f : a.lamG;
-                update_vec<MOM, V>(xv[u], gv[u], mv[u], zl, zg, c);
-                st_stream(a.x + o, xv[u]);
-                if (MOM) st_stream(a.m + o, mv[u]);
-                if (a.xb) st_bf16(a.xb + o, xv[u]);
-            }
-        }
-        for (; i < r1; ++i) {
-            const int64_t o = (int64_t)i * a.ld + col;
-            V xv = ld_vec<VEC>(a.x + o);
-            V gv = ld_stream<VEC>(a.g + o);
-            V mv = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
-            c.cL = (exempt && i == ll) ? 0.0f : a.lamL;
-            c.cG = (exempt && i == gl) ? 0.0f : a.lamG;
-            update_vec<MOM, V>(xv, gv, mv, zl, zg, c);
-            st_stream(a.x + o, xv);
-            if (MOM) st_stream(a.m + o, mv);
-            if (a.xb) st_bf16(a.xb + o, xv);
-        }
+        V zl = zero_of(V());
+        if (pullL) zl = (ll == gl) ? zg : ld_vec<VEC>((a.refreshed[j] ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
+        Coef cg = c;
+        if (exempt) { cg.cG = 0.0f; if (ll == gl) cg.cL = 0.0f; }
+        update_row<VEC, MOM>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);
     }
-}
-
-__global__ void clear_refreshed_kernel(int32_t* refreshed, int G)
-{
-    int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t <= G) refreshed[t] = 0;
+    if (!pullL) return;
+    for (int j = 0; j < a.G; ++j) {
+        if (!a.refreshed[j]) continue;
+        const int ll = a.lead[j];
+        if (freshG && ll == gl) {          // already updated above; its pre-update tile is zg
+            if (a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, zg);
+            continue;
+        }
+        const int64_t o = (int64_t)ll * a.ld + col;
+        V xv = ld_vec<VEC>(a.x + o);
+        if (a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, xv);
+        Coef cl = c;
+        if (exempt) { cl.cL = 0.0f; if (ll == gl) cl.cG = 0.0f; }
+        update_row<VEC, MOM>(a, o, xv, xv, zg, cl);
+    }
 }
 
 template <int VEC, bool MOM>
-static void launch_range(PullDev a, hipStream_t s)
+static void launch_range(PullDev a, bool leaders, hipStream_t s)
 {
     const int64_t cols = a.col1 - a.col0;
     if (cols <= 0) return;
     const int64_t per_block = (int64_t)kPullThreads * VEC;
-    const int64_t blocks = (cols + per_block - 1) / per_block;
-    hipLaunchKernelGGL((pull_update_kernel<VEC, MOM, 4>), dim3((unsigned)blocks), dim3(kPullThreads), 0, s, a);
+    const int64_t tiles = (cols + per_block - 1) / per_block;
+    hipLaunchKernelGGL((pull_rows_kernel<VEC, MOM>), dim3((unsigned)tiles, (unsigned)a.W), dim3(kPullThreads), 0, s, a);
+    if (leaders)
+        hipLaunchKernelGGL((pull_leaders_kernel<VEC, MOM>), dim3((unsigned)tiles), dim3(kPullThreads), 0, s, a);
 }
 
 hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s)
@@ -191,22 +228,20 @@ hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStr
     a.ld = p.ld; a.W = p.W; a.G = p.G;
     a.eta = p.eta; a.lamL = p.lamL; a.lamG = p.lamG; a.mu = p.mu; a.wd = p.wd;
     a.flags = p.flags; a.use_refreshed = p.use_refreshed;
-    a.offsets = st.offsets; a.lead = st.lead; a.glead = st.glead; a.refreshed = st.refreshed;
+    a.offsets = st.offsets; a.group_of = st.group_of; a.lead = st.lead; a.glead = st.glead; a.refreshed = st.refreshed;
     const bool mom = p.mu != 0.0f;
+    const bool leaders = p.use_refreshed && (p.lamL != 0.0f || p.lamG != 0.0f);
 
     auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
     const bool vec_ok = (p.ld % 4 == 0) && aligned16(p.x) && aligned16(p.g) && (!mom || aligned16(p.m)) &&
                         (!p.Z || aligned16(p.Z)) && (!p.xb || (reinterpret_cast<uintptr_t>(p.xb) & 7u) == 0);
     const int64_t P4 = vec_ok ? (p.P & ~(int64_t)3) : 0;
-    // whole v4f columns, then the ragged tail (or everything) element-wise
+    // whole float4 columns, then the ragged tail (or everything) element-wise;
+    // the two column ranges are disjoint, so their launches are independent
     a.col0 = 0; a.col1 = P4;
-    if (mom) launch_range<4, true>(a, s); else launch_range<4, false>(a, s);
+    if (mom) launch_range<4, true>(a, leaders, s); else launch_range<4, false>(a, leaders, s);
     a.col0 = P4; a.col1 = p.P;
-    if (mom) launch_range<1, true>(a, s); else launch_range<1, false>(a, s);
-    if (p.clear_refreshed) {
-        int threads = 256, blocks = (p.G + 1 + threads - 1) / threads;
-        hipLaunchKernelGGL(clear_refreshed_kernel, dim3(blocks), dim3(threads), 0, s, st.refreshed, p.G);
-    }
+    if (mom) launch_range<1, true>(a, leaders, s); else launch_range<1, false>(a, leaders, s);
     return hipGetLastError();
 }
 
