@@ -1,19 +1,512 @@
-// MLP gradients: placeholder until the MFMA kernels land.
+// Per-worker gradient and loss of a fully connected ReLU classifier with softmax
+// cross-entropy, for all W workers of the population at once (each worker has
+// its own weights).  This is the "stochastic gradient g_t^{j,i} on the
+// worker's own minibatch" of arXiv 1905.10395 (Section 2) for the MLP
+// workload: bf16 matrix operands, fp32 accumulation, fp32 gradients.
+//
+//   forward   z_k = h_{k-1} W_k^T + b_k ; h_k = bf16(relu(z_k)) ; logits fp32
+//   loss      mean_b (logsumexp(z_L) - z_L[y_b]) ; delta_L = bf16((softmax - onehot)/B)
+//   backward  dW_k = delta_k^T h_{k-1} ; db_k = sum_b delta_k ;
+//             delta_{k-1} = bf16((delta_k W_k) .* [h_{k-1} > 0])
+//
+// The three matrix products are dense contractions and run on the matrix
+// cores (v_mfma_f32_32x32x16_bf16) whenever the shapes are multiples of the
+// tile sizes; a plain vector-ALU path covers every other shape, including
+// the narrow classifier layer.
+//
+// Operand layouts for the MFMA kernel.  A lane feeds the matrix core eight
+// consecutive values along the contraction index, so each operand must be
+// contiguous along that index in LDS:
+//   forward : A = h_{k-1} [B][d_in]   B-operand = W_k [d_out][d_in]    both contiguous in d_in
+//   d-input : A = delta_k [B][d_out]  B-operand = W_k [d_out][d_in]    contraction over d_out: rows of W
+//   d-weight: A = delta_k^T [d_out][B] B-operand = h_{k-1} [B][d_in]   contraction over B: rows of h
+// In the last two the B-operand is contiguous along the *output* column, so
+// its tile is transposed on the way from global memory into LDS (a 4x8 or 2x8
+// register micro-transpose per thread).  delta_k is stored in both layouts by
+// the kernel that produces it.
 #include "common.h"
 
 namespace lsgd {
 
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+enum { EPI_FWD = 0, EPI_DX = 1, EPI_DW = 2 };
+
+struct GemmArgs {
+    const uint16_t* A; int64_t sA; int64_t lda;   // [M][K], per-worker stride sA (elements)
+    const uint16_t* B; int64_t sB; int64_t ldb;   // TRANS_B ? [K][N] : [N][K]
+    int M, N, K;
+    const float* bias; int64_t sBias;             // EPI_FWD: fp32 [N]
+    const uint16_t* mask; int64_t sMask; int64_t ldmask; // EPI_DX: h_{k-1} [M][N]
+    uint16_t* out; int64_t sOut; int64_t ldout;   // EPI_FWD: h [M][N]; EPI_DX: delta [M][N]
+    uint16_t* outT; int64_t sOutT; int64_t ldoutT;// EPI_DX: delta^T [N][M]
+    float* C; int64_t sC; int64_t ldc;            // EPI_DW: fp32 [M][N]
+};
+
+constexpr int kGemmThreads = 256;
+constexpr int kBK = 64;          // contraction tile
+constexpr int kLdk = kBK + 8;    // padded LDS row (bf16 elements): 144 B
+
+// 16-byte chunk position inside an LDS row; rows of a transposed-staged tile
+// are swizzled so that the transposing 8-byte writes spread over all banks.
+template <bool SWZ> __device__ __forceinline__ int lds_chunk(int row, int chunk)
+{
+    return SWZ ? (chunk ^ ((row >> 3) & 7)) : chunk;
+}
+
+template <int BM, int BN, bool TRANS_B, int EPI>
+__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
+{
+    constexpr int WTM = BM / 2, WTN = BN / 2;        // 2 x 2 wavefronts
+    constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wavefront
+    constexpr int A_CHUNKS = BM * (kBK / 8) / kGemmThreads; // 16-byte chunks per thread
+    constexpr int B_CHUNKS = BN * (kBK / 8) / kGemmThreads;
+    constexpr int KK = BN / 32;                      // k-rows per thread in the transposing stage
+
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t* As = smem;                              // [2][BM][kLdk]
+    uint16_t* Bs = smem + 2 * BM * kLdk;              // [2][BN][kLdk]
+
+    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    const int wm = wid >> 1, wn = wid & 1;
+    const int w = blockIdx.z;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const uint16_t* A = g.A + (int64_t)w * g.sA + (int64_t)m0 * g.lda;
+    const uint16_t* B = g.B + (int64_t)w * g.sB;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    u32x4 ra[A_CHUNKS];
+    u32x4 rb[TRANS_B ? KK : B_CHUNKS];
+
+    auto load_global = [&](int kt) {
+        const int k0 = kt * kBK;
+#pragma unroll
+        for (int c = 0; c < A_CHUNKS; ++c) {
+            const int id = tid + c * kGemmThreads, row = id >> 3, ch = id & 7;
+            ra[c] = *reinterpret_cast<const u32x4*>(A + (int64_t)row * g.lda + k0 + ch * 8);
+        }
+        if (TRANS_B) {
+            const int ng = tid % (BN / 8), kg = tid / (BN / 8);
+#pragma unroll
+            for (int q = 0; q < KK; ++q)
+                rb[q] = *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + kg * KK + q) * g.ldb + n0 + ng * 8);
+        } else {
+#pragma unroll
+            for (int c = 0; c < B_CHUNKS; ++c) {
+                const int id = tid + c * kGemmThreads, row = id >> 3, ch = id & 7;
+                rb[c] = *reinterpret_cast<const u32x4*>(B + (int64_t)(n0 + row) * g.ldb + k0 + ch * 8);
+            }
+        }
+    };
+    auto store_lds = [&](int buf) {
+        uint16_t* as = As + buf * BM * kLdk;
+        uint16_t* bs = Bs + buf * BN * kLdk;
+#pragma unroll
+        for (int c = 0; c < A_CHUNKS; ++c) {
+            const int id = tid + c * kGemmThreads, row = id >> 3, ch = id & 7;
+            *reinterpret_cast<u32x4*>(as + row * kLdk + ch * 8) = ra[c];
+        }
+        if (TRANS_B) {
+            const int ng = tid % (BN / 8), kg = tid / (BN / 8);
+            const int kk0 = kg * KK;               // first k of this thread's micro-tile
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                // element (q, n) of the micro-tile is the (n&1) half of dword n/2 of rb[q]
+                uint32_t v[KK];
+#pragma unroll
+                for (int q = 0; q < KK; ++q) v[q] = (n & 1) ? (rb[q][n >> 1] >> 16) : (rb[q][n >> 1] & 0xFFFFu);
+                const int row = ng * 8 + n;
+                uint16_t* dst = bs + row * kLdk + lds_chunk<true>(row, kk0 >> 3) * 8 + (kk0 & 7);
+                if (KK == 4) {
+                    u32x2 o = {v[0] | (v[1] << 16), v[2] | (v[3] << 16)};
+                    *reinterpret_cast<u32x2*>(dst) = o;
+                } else {
+                    *reinterpret_cast<uint32_t*>(dst) = v[0] | (v[1] << 16);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < B_CHUNKS; ++c) {
+                const int id = tid + c * kGemmThreads, row = id >> 3, ch = id & 7;
+                *reinterpret_cast<u32x4*>(bs + row * kLdk + ch * 8) = rb[c];
+            }
+        }
+    };
+
+    const int nk = g.K / kBK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_global(kt + 1);
+        const uint16_t* as = As + buf * BM * kLdk;
+        const uint16_t* bs = Bs + buf * BN * kLdk;
+#pragma unroll
+        for (int kk = 0; kk < kBK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
+            const int ch = kk * 2 + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row = wm * WTM + i * 32 + (lane & 31);
+                af[i] = *reinterpret_cast<const bf16x8*>(as + row * kLdk + ch * 8);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int row = wn * WTN + j * 32 + (lane & 31);
+                bfr[j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + lds_chunk<TRANS_B>(row, ch) * 8);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: lane holds column n = lane%32 and rows (lane/32)*4 + 8*(v/4) + v%4 of each 32x32 tile
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * WTN + j * 32 + (lane & 31);
+            const int mb = m0 + wm * WTM + i * 32 + (lane >> 5) * 4;
+            if (EPI == EPI_FWD) {
+                const float b = g.bias[(int64_t)w * g.sBias + n];
+                uint16_t* out = g.out + (int64_t)w * g.sOut;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = mb + 8 * (v >> 2) + (v & 3);
+                    float z = acc[i][j][v] + b;
+                    out[(int64_t)m * g.ldout + n] = f32_to_bf16_rne(z > 0.f ? z : 0.f);
+                }
+            } else if (EPI == EPI_DX) {
+                const uint16_t* mask = g.mask + (int64_t)w * g.sMask;
+                uint16_t* out = g.out + (int64_t)w * g.sOut;
+                uint16_t* outT = g.outT + (int64_t)w * g.sOutT;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t pk[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int m = mb + 8 * q + r;
+                        const bool on = mask[(int64_t)m * g.ldmask + n] != 0;
+                        const uint16_t d = on ? f32_to_bf16_rne(acc[i][j][q * 4 + r]) : (uint16_t)0;
+                        out[(int64_t)m * g.ldout + n] = d;
+                        pk[r] = d;
+                    }
+                    u32x2 o = {pk[0] | (pk[1] << 16), pk[2] | (pk[3] << 16)};
+                    *reinterpret_cast<u32x2*>(outT + (int64_t)n * g.ldoutT + mb + 8 * q) = o;
+                }
+            } else {
+                float* C = g.C + (int64_t)w * g.sC;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = mb + 8 * (v >> 2) + (v & 3);
+                    __builtin_nontemporal_store(acc[i][j][v], C + (int64_t)m * g.ldc + n);
+                }
+            }
+        }
+}
+
+template <int BM, int BN, bool TRANS_B, int EPI>
+static void launch_gemm(const GemmArgs& g, int W, hipStream_t s)
+{
+    const size_t lds = (size_t)2 * (BM + BN) * kLdk * sizeof(uint16_t);
+    static bool configured = false;
+    if (!configured) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, TRANS_B, EPI>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        configured = true;
+    }
+    dim3 grid((unsigned)(g.N / BN), (unsigned)(g.M / BM), (unsigned)W);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, TRANS_B, EPI>), grid, dim3(kGemmThreads), lds, s, g);
+}
+
+static bool aligned_for_mfma(const GemmArgs& g, bool trans_b)
+{
+    auto a16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+    bool ok = a16(g.A) && a16(g.B) && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.sA % 8 == 0 && g.sB % 8 == 0;
+    (void)trans_b;
+    return ok;
+}
+
+// Picks a tile so that the grid fills the chip; returns false when no MFMA tile fits the shape.
+template <bool TRANS_B, int EPI>
+static bool try_mfma(const GemmArgs& g, int W, hipStream_t s)
+{
+    if (g.K % kBK || g.M % 128 || g.N % 64 || !aligned_for_mfma(g, TRANS_B)) return false;
+    if (EPI == EPI_DX && (g.ldoutT % 4 || (reinterpret_cast<uintptr_t>(g.outT) & 7u) || g.sOutT % 4)) return false;
+    const int64_t blocks128 = (int64_t)(g.M / 128) * (g.N / 128) * W;
+    if (g.N % 128 == 0 && blocks128 >= 256) launch_gemm<128, 128, TRANS_B, EPI>(g, W, s);
+    else launch_gemm<128, 64, TRANS_B, EPI>(g, W, s);
+    return true;
+}
+
+// ------------------------------------------------------------------------------------------
+// Vector-ALU kernels: any shape.  They are the path of the narrow classifier layer and the
+// fallback of shapes the MFMA tiles do not divide.
+// ------------------------------------------------------------------------------------------
+
+// out[b][o] = sum_i h[b][i] * Wq[o][i] + bias[o].  One wavefront per (b, worker); lanes stride over i.
+// HIDDEN: relu + bf16 store; else fp32 logits.
+template <bool HIDDEN>
+__global__ __launch_bounds__(256) void fwd_valu_kernel(const uint16_t* __restrict__ H, int64_t sH, int64_t ldh,
+                                                       const uint16_t* __restrict__ Wq, int64_t sW, const float* __restrict__ bias,
+                                                       int64_t sBias, int B, int din, int dout, uint16_t* __restrict__ out,
+                                                       float* __restrict__ logits, int64_t sOut, int64_t ldout)
+{
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int w = blockIdx.y;
+    if (b >= B) return;
+    const uint16_t* h = H + (int64_t)w * sH + (int64_t)b * ldh;
+    const uint16_t* Wm = Wq + (int64_t)w * sW;
+    for (int o = 0; o < dout; ++o) {
+        const uint16_t* wr = Wm + (int64_t)o * din;
+        float acc = 0.f;
+        for (int i = lane; i < din; i += 64) acc = fmaf(bf16_to_f32(h[i]), bf16_to_f32(wr[i]), acc);
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+        if (lane == 0) {
+            const float z = acc + bias[(int64_t)w * sBias + o];
+            if (HIDDEN) out[(int64_t)w * sOut + (int64_t)b * ldout + o] = f32_to_bf16_rne(z > 0.f ? z : 0.f);
+            else logits[(int64_t)w * sOut + (int64_t)b * ldout + o] = z;
+        }
+    }
+}
+
+// Softmax cross-entropy of one worker's batch: loss = mean_b(lse - z[y]); delta = bf16((p - onehot)/B),
+// stored as [B][C] and [C][B].  One workgroup per worker.
+__global__ __launch_bounds__(256) void loss_delta_kernel(const float* __restrict__ logits, int64_t sLogits, const int32_t* __restrict__ y,
+                                                         int B, int C, uint16_t* __restrict__ delta, uint16_t* __restrict__ deltaT,
+                                                         int64_t sDelta, float* __restrict__ losses)
+{
+    const int w = blockIdx.x;
+    const float* lg = logits + (int64_t)w * sLogits;
+    uint16_t* d = delta + (int64_t)w * sDelta;
+    uint16_t* dT = deltaT + (int64_t)w * sDelta;
+    const float invB = 1.0f / (float)B;
+    double part = 0.0;
+    for (int b = threadIdx.x; b < B; b += 256) {
+        const float* z = lg + (int64_t)b * C;
+        float mx = z[0];
+        for (int c = 1; c < C; ++c) mx = fmaxf(mx, z[c]);
+        float se = 0.f;
+        for (int c = 0; c < C; ++c) se += expf(z[c] - mx);
+        const float lse = mx + logf(se);
+        const int yb = y[(int64_t)w * B + b];
+        part += (double)(lse - z[yb]);
+        for (int c = 0; c < C; ++c) {
+            const float p = expf(z[c] - lse);
+            const uint16_t q = f32_to_bf16_rne((p - (c == yb ? 1.f : 0.f)) * invB);
+            d[(int64_t)b * C + c] = q;
+            dT[(int64_t)c * B + b] = q;
+        }
+    }
+    __shared__ double red[256];
+    red[threadIdx.x] = part;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) losses[w] = (float)(red[0] / (double)B);
+}
+
+// dW[o][i] = sum_b deltaT[o][b] * h[b][i].  One thread per (o, i).
+__global__ __launch_bounds__(256) void dw_valu_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, const uint16_t* __restrict__ H,
+                                                      int64_t sH, int64_t ldh, int B, int din, int dout, float* __restrict__ g, int64_t sG)
+{
+    const int w = blockIdx.z, o = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= din) return;
+    const uint16_t* dt = deltaT + (int64_t)w * sD + (int64_t)o * B;
+    const uint16_t* h = H + (int64_t)w * sH;
+    float acc = 0.f;
+    for (int b = 0; b < B; ++b) acc = fmaf(bf16_to_f32(dt[b]), bf16_to_f32(h[(int64_t)b * ldh + i]), acc);
+    g[(int64_t)w * sG + (int64_t)o * din + i] = acc;
+}
+
+// db[o] = sum_b deltaT[o][b].  One wavefront per o.
+__global__ __launch_bounds__(256) void db_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, int B, int dout, float* __restrict__ g, int64_t sG)
+{
+    const int lane = threadIdx.x & 63;
+    const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int w = blockIdx.y;
+    if (o >= dout) return;
+    const uint16_t* dt = deltaT + (int64_t)w * sD + (int64_t)o * B;
+    float acc = 0.f;
+    for (int b = lane; b < B; b += 64) acc += bf16_to_f32(dt[b]);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+    if (lane == 0) g[(int64_t)w * sG + o] = acc;
+}
+
+// dprev[b][i] = bf16((sum_o delta[b][o] * Wq[o][i]) * [h[b][i] > 0]), also stored transposed.  One thread per (b, i).
+__global__ __launch_bounds__(256) void dx_valu_kernel(const uint16_t* __restrict__ delta, int64_t sD, const uint16_t* __restrict__ Wq, int64_t sW,
+                                                      const uint16_t* __restrict__ H, int64_t sH, int64_t ldh, int B, int din, int dout,
+                                                      uint16_t* __restrict__ dprev, uint16_t* __restrict__ dprevT, int64_t sP)
+{
+    const int w = blockIdx.z, b = blockIdx.y;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= din) return;
+    const uint16_t* d = delta + (int64_t)w * sD + (int64_t)b * dout;
+    const uint16_t* Wm = Wq + (int64_t)w * sW;
+    float acc = 0.f;
+    for (int o = 0; o < dout; ++o) acc = fmaf(bf16_to_f32(d[o]), bf16_to_f32(Wm[(int64_t)o * din + i]), acc);
+    const bool on = H[(int64_t)w * sH + (int64_t)b * ldh + i] != 0;
+    const uint16_t q = on ? f32_to_bf16_rne(acc) : (uint16_t)0;
+    dprev[(int64_t)w * sP + (int64_t)b * din + i] = q;
+    dprevT[(int64_t)w * sP + (int64_t)i * B + b] = q;
+}
+
+__global__ __launch_bounds__(256) void zero_pad_kernel(float* __restrict__ g, int64_t P, int64_t ld)
+{
+    const int64_t c = P + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c < ld) g[(int64_t)blockIdx.y * ld + c] = 0.f;
+}
+
+// ------------------------------------------------------------------------------------------
+// Host orchestration
+// ------------------------------------------------------------------------------------------
+namespace {
+
+struct MlpPlan {
+    int L;
+    std::size_t bytes;
+    // per-worker element offsets inside the scratch (bf16 elements unless noted)
+    int64_t h[64];      // h[k], k = 1..L-1  [B][d_k]
+    int64_t d[64];      // delta[k], k = 1..L [B][d_k]
+    int64_t dT[64];     // delta^T[k]         [d_k][B]
+    int64_t logits;     // fp32 [B][C], offset in bytes from the worker's base
+    int64_t per_worker; // bytes per worker
+};
+
+inline int64_t up16(int64_t v) { return (v + 15) / 16 * 16; }
+
+MlpPlan make_plan(const lsgd_mlp_batch& b, int W)
+{
+    MlpPlan p{};
+    p.L = b.n_layers;
+    int64_t o = 0; // bytes
+    for (int k = 1; k <= p.L; ++k) {
+        const int64_t n = (int64_t)b.B * b.dims[k] * 2;
+        if (k < p.L) { p.h[k] = o / 2; o = up16(o + n); }
+        p.d[k] = o / 2; o = up16(o + n);
+        p.dT[k] = o / 2; o = up16(o + n);
+    }
+    p.logits = o; o = up16(o + (int64_t)b.B * b.dims[p.L] * 4);
+    p.per_worker = (o + 255) / 256 * 256;
+    p.bytes = (std::size_t)p.per_worker * (std::size_t)W;
+    return p;
+}
+
+} // namespace
+
 bool mlp_shape_supported(const lsgd_mlp_batch& b, const char** why)
 {
-    (void)b;
-    *why = "MLP gradient kernels are not built yet";
-    return false;
+    if (b.n_layers > 60) { *why = "more than 60 layers"; return false; }
+    if (b.dims[b.n_layers] > 4096) { *why = "more than 4096 classes"; return false; }
+    return true;
 }
-size_t mlp_scratch_bytes(int W, const lsgd_mlp_batch& b) { (void)W; (void)b; return 0; }
-hipError_t launch_mlp_grad_loss(const uint16_t*, const float*, float*, float*, int, int64_t, int64_t,
-                                const lsgd_mlp_batch&, const DeviceState&, hipStream_t)
+
+size_t mlp_scratch_bytes(int W, const lsgd_mlp_batch& b) { return make_plan(b, W).bytes; }
+
+hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, float* losses, int W, int64_t P,
+                                int64_t ld, const lsgd_mlp_batch& b, const DeviceState& st, hipStream_t s)
 {
-    return hipErrorNotSupported;
+    const MlpPlan p = make_plan(b, W);
+    const int L = p.L, B = b.B;
+    uint16_t* sc16 = reinterpret_cast<uint16_t*>(st.scratch);
+    const int64_t sW16 = p.per_worker / 2;     // per-worker stride in bf16 elements
+    const int64_t sW32 = p.per_worker / 4;     // ... in fp32 elements
+    float* logits = reinterpret_cast<float*>(st.scratch + p.logits);
+
+    int64_t woff[64];
+    { int64_t o = 0; for (int k = 1; k <= L; ++k) { woff[k] = o; o += (int64_t)b.dims[k] * b.dims[k - 1] + b.dims[k]; } }
+
+    // ---- forward ----
+    for (int k = 1; k <= L; ++k) {
+        const int din = b.dims[k - 1], dout = b.dims[k];
+        const uint16_t* Hin = (k == 1) ? b.X : sc16 + p.h[k - 1];
+        const int64_t sHin = (k == 1) ? (int64_t)B * din : sW16;
+        const float* bias = x + woff[k] + (int64_t)dout * din;
+        bool done = false;
+        if (k < L) {
+            GemmArgs a{};
+            a.A = Hin; a.sA = sHin; a.lda = din;
+            a.B = xb + woff[k]; a.sB = ld; a.ldb = din;
+            a.M = B; a.N = dout; a.K = din;
+            a.bias = bias; a.sBias = ld;
+            a.out = sc16 + p.h[k]; a.sOut = sW16; a.ldout = dout;
+            done = try_mfma<false, EPI_FWD>(a, W, s);
+        }
+        if (!done) {
+            dim3 grid((unsigned)((B + 3) / 4), (unsigned)W);
+            if (k < L)
+                hipLaunchKernelGGL(fwd_valu_kernel<true>, grid, dim3(256), 0, s, Hin, sHin, (int64_t)din, xb + woff[k], ld, bias, ld,
+                                   B, din, dout, sc16 + p.h[k], (float*)nullptr, sW16, (int64_t)dout);
+            else
+                hipLaunchKernelGGL(fwd_valu_kernel<false>, grid, dim3(256), 0, s, Hin, sHin, (int64_t)din, xb + woff[k], ld, bias, ld,
+                                   B, din, dout, (uint16_t*)nullptr, logits, sW32, (int64_t)dout);
+        }
+    }
+    // ---- loss and output delta ----
+    hipLaunchKernelGGL(loss_delta_kernel, dim3((unsigned)W), dim3(256), 0, s, logits, sW32, b.y, B, b.dims[L],
+                       sc16 + p.d[L], sc16 + p.dT[L], sW16, losses);
+    // ---- backward ----
+    for (int k = L; k >= 1; --k) {
+        const int din = b.dims[k - 1], dout = b.dims[k];
+        const uint16_t* Hin = (k == 1) ? b.X : sc16 + p.h[k - 1];
+        const int64_t sHin = (k == 1) ? (int64_t)B * din : sW16;
+        // dW_k
+        {
+            GemmArgs a{};
+            a.A = sc16 + p.dT[k]; a.sA = sW16; a.lda = B;
+            a.B = Hin; a.sB = sHin; a.ldb = din;
+            a.M = dout; a.N = din; a.K = B;
+            a.C = g + woff[k]; a.sC = ld; a.ldc = din;
+            if (!try_mfma<true, EPI_DW>(a, W, s)) {
+                dim3 grid((unsigned)((din + 255) / 256), (unsigned)dout, (unsigned)W);
+                hipLaunchKernelGGL(dw_valu_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
+                                   dout, g + woff[k], ld);
+            }
+        }
+        // db_k
+        hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, sc16 + p.dT[k], sW16, B, dout,
+                           g + woff[k] + (int64_t)dout * din, ld);
+        // delta_{k-1}
+        if (k > 1) {
+            GemmArgs a{};
+            a.A = sc16 + p.d[k]; a.sA = sW16; a.lda = dout;
+            a.B = xb + woff[k]; a.sB = ld; a.ldb = din;
+            a.M = B; a.N = din; a.K = dout;
+            a.mask = Hin; a.sMask = sHin; a.ldmask = din;
+            a.out = sc16 + p.d[k - 1]; a.sOut = sW16; a.ldout = din;
+            a.outT = sc16 + p.dT[k - 1]; a.sOutT = sW16; a.ldoutT = B;
+            if (!try_mfma<true, EPI_DX>(a, W, s)) {
+                dim3 grid((unsigned)((din + 255) / 256), (unsigned)B, (unsigned)W);
+                hipLaunchKernelGGL(dx_valu_kernel, grid, dim3(256), 0, s, sc16 + p.d[k], sW16, xb + woff[k], ld, Hin, sHin,
+                                   (int64_t)din, B, din, dout, sc16 + p.d[k - 1], sc16 + p.dT[k - 1], sW16);
+            }
+        }
+    }
+    if (ld > P)
+        hipLaunchKernelGGL(zero_pad_kernel, dim3((unsigned)((ld - P + 255) / 256), (unsigned)W), dim3(256), 0, s, g, P, ld);
+    return hipGetLastError();
 }
 
 } // namespace lsgd

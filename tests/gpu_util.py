@@ -62,14 +62,15 @@ class Pair:
             ok = False
         return ok
 
-    def check_state(self, tol, what=""):
+    def check_state(self, tol, what="", tol_m=None):
         torch.cuda.synchronize()
         P = self.P
         ex = rel_l2_rows(self.x.cpu().numpy()[:, :P], self.ora.x[:, :P])
         assert ex.max() <= tol, f"{what} x rel-L2 {ex.max():.3e} > {tol}"
         if self.m is not None:
             em = rel_l2_rows(self.m.cpu().numpy()[:, :P], self.ora.m[:, :P])
-            assert em.max() <= tol, f"{what} m rel-L2 {em.max():.3e} > {tol}"
+            tm = tol if tol_m is None else tol_m
+            assert em.max() <= tm, f"{what} m rel-L2 {em.max():.3e} > {tm}"
         return ex.max()
 
     def resync_from_oracle(self):

@@ -1,0 +1,113 @@
+"""GPU parity: MLP gradients (MFMA and vector-ALU paths) and whole LSGD steps with momentum and the
+bf16 shadow, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_1905_10395_amd as L
+from gpu_util import DEV, Pair, dev, rel_l2_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def make(dims, W, B, seed, momentum=0.0, flags=0, G=1, bias_std=0.05):
+    P = wl.mlp_param_count(dims)
+    ld = wl.padded_ld(P)
+    x0 = wl.mlp_init(W, dims, ld=ld, seed=seed, bias_std=bias_std)
+    means = wl.gmm_means(dims[0], dims[-1], seed=seed)
+    Xb, y = wl.gmm_batch(W, B, means, 0, seed=seed)
+    Xd = dev(Xb.view(np.int16)).view(torch.bfloat16)
+    yd = dev(y)
+    batch = L.MLPBatch(dims, Xd, yd)
+    pr = Pair(x0, wl.equal_group_offsets(W, G), P=P, momentum=momentum, flags=flags, shadow=True, largest_batch=batch)
+    return pr, batch, Xb, y, P, means
+
+
+# Gradient tolerance.  Activations and deltas are quantised to bf16 (8 significant bits) and the ReLU mask is a
+# sign decision; the GPU takes those decisions on fp32-accumulated sums, the oracle on fp64-accumulated ones, so
+# a value that lies within fp32 rounding of a bf16 tie or of zero may legitimately fall the other way.  One such
+# event moves one activation by one bf16 ulp (2^-8 relative) or switches one unit of one sample on or off, which
+# shows as an isolated deviation in one worker.  Hence: the typical (median) worker must agree to 1e-4, and no
+# worker may deviate by more than 2e-3 (half a bf16 ulp of the operands) in relative L2.
+GRAD_TOL_MEDIAN, GRAD_TOL_MAX = 1e-4, 2e-3
+
+
+def per_layer_errors(g_gpu, g_ora, dims):
+    """(median, max) over workers of the relative L2 error, per parameter block (W_k, b_k)"""
+    med, mx, off = [], [], 0
+    for k in range(len(dims) - 1):
+        for n in (dims[k + 1] * dims[k], dims[k + 1]):
+            e = rel_l2_rows(g_gpu[:, off:off + n], g_ora[:, off:off + n])
+            med.append(np.median(e)); mx.append(e.max()); off += n
+    return med, mx
+
+
+def check_grads(g_gpu, g_ora, dims):
+    med, mx = per_layer_errors(g_gpu, g_ora, dims)
+    assert max(med) < GRAD_TOL_MEDIAN, med
+    assert max(mx) < GRAD_TOL_MAX, mx
+
+
+SHAPES = [
+    ([12, 16, 5], 2, 9),                      # tiny, vector-ALU path everywhere
+    ([20, 24, 16, 8, 4], 3, 13),              # 4 layers, ragged
+    ([192, 256, 128, 10], 3, 128),            # MFMA 128x64 tiles: forward, d-input, d-weight
+    ([512, 1024, 10], 8, 128),                # d-weight on 128x128 tiles
+    ([64, 512, 256, 10], 64, 128),            # forward and d-input on 128x128 tiles
+    ([128, 128, 10], 2, 256),                 # two M tiles, K = 256 for d-weight
+]
+
+
+@pytest.mark.parametrize("dims,W,B", SHAPES)
+def test_mlp_grad_loss_matches_oracle(dims, W, B):
+    pr, batch, Xb, y, P, _ = make(dims, W, B, seed=len(dims) * 100 + W)
+    pr.g.fill_(7.0)
+    pr.ora.grad_loss_mlp(dims, Xb, y)
+    pr.pop.grad_loss(batch)
+    torch.cuda.synchronize()
+    g = pr.g.cpu().numpy()
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
+    check_grads(g[:, :P], pr.ora.g[:, :P], dims)
+    assert np.all(g[:, P:] == 0)
+
+
+def test_mlp_lsgd_steps_with_momentum_and_shadow():
+    """16 workers in 4 groups, momentum 0.9, lam_L 0.1, lam_G 0.05, leaders every step; the bf16 operands
+    of step t+1 come from the shadow written by the update of step t."""
+    dims, W, G, B = [192, 256, 10], 16, 4, 128
+    pr, _, _, _, P, means = make(dims, W, B, seed=77, momentum=0.9, flags=L.WRITE_BF16_SHADOW, G=G)
+    steps = 12
+    for t in range(steps):
+        Xb, y = wl.gmm_batch(W, B, means, t, seed=77)
+        batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+        pr.ora.grad_loss_mlp(dims, Xb, y)
+        pr.ora.select(); pr.ora.update(0.01, 0.1, 0.05)
+        pr.pop.step(batch, 0.01, 0.1, 0.05)
+        if not pr.check_leaders():
+            pr.resync_from_oracle()
+        if t == 0:
+            np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
+            pr.check_state(1e-4, "step 0", tol_m=GRAD_TOL_MAX)
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-3)
+    pr.check_state(1e-3, f"after {steps} steps", tol_m=GRAD_TOL_MAX)
+    # the shadow is exactly bf16(x) of the GPU's own master weights
+    xb = pr.xb.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(xb[:, :P], wl.to_bf16_bits(pr.x.cpu().numpy()[:, :P]))
+
+
+def test_mlp_two_layer_config_full_size_one_step():
+    """2-layer MLP 3072-1024-10, W=16 in 4 groups, batch 128, momentum 0.9, lam_L 0.1, lam_G 0.05: one whole
+    step at full size against the oracle."""
+    dims, W, G, B = [3072, 1024, 10], 16, 4, 128
+    pr, batch, Xb, y, P, _ = make(dims, W, B, seed=3, momentum=0.9, flags=L.WRITE_BF16_SHADOW, G=G, bias_std=0.0)
+    pr.ora.grad_loss_mlp(dims, Xb, y)
+    pr.ora.select(); pr.ora.update(0.01, 0.1, 0.05)
+    pr.pop.step(batch, 0.01, 0.1, 0.05)
+    assert pr.check_leaders()
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
+    check_grads(pr.g.cpu().numpy()[:, :P], pr.ora.g[:, :P], dims)
+    # parameters to 1e-4; the momentum buffer after one step is the gradient plus pulls, so it
+    # inherits the gradient's tolerance
+    pr.check_state(1e-4, "full-size step", tol_m=GRAD_TOL_MAX)
