@@ -192,12 +192,110 @@ def cpu_c2(data):
             "sample": f"the full workload (all {W} workers, B={B}), {reps} whole steps"}
 
 
+# ------------------------------------------------------------------------------------------
+# C3 / C5: MLP classifier on Gaussian-mixture batches (whole step, bf16 operands, fp32 master)
+# ------------------------------------------------------------------------------------------
+MLP_CFG = {
+    "c3": dict(dims=[3072, 1024, 10], W=16, G=4, B=128, tau=1, staggered=False, lamL=0.1, lamG=0.05, K=4,
+               name="2-layer MLP 3072-1024-10"),
+    "c5": dict(dims=[3072, 4096, 4096, 4096, 10], W=8, G=2, B=256, tau=64, staggered=True, lamL=0.1, lamG=0.02, K=2,
+               name="4-layer MLP 3072-4096-4096-4096-10"),
+}
+
+
+def mlp_flops(dims, B):
+    """forward + d-weight for every layer, + d-input for every layer but the first (2 flops per MAC)"""
+    f = 0
+    for k in range(len(dims) - 1):
+        f += 2 * 2 * B * dims[k] * dims[k + 1]
+        if k > 0:
+            f += 2 * B * dims[k] * dims[k + 1]
+    return f
+
+
+def make_mlp(cfg):
+    dims, W, B, K = cfg["dims"], cfg["W"], cfg["B"], cfg["K"]
+    P = wl.mlp_param_count(dims)
+    ld = wl.padded_ld(P)
+    x0 = wl.mlp_init(W, dims, ld=ld)
+    means = wl.gmm_means(dims[0], dims[-1])
+    batches = [wl.gmm_batch(W, B, means, t) for t in range(K)]
+    return P, ld, x0, batches
+
+
+def run_mlp(L, steps, warmup, cfg, data):
+    dims, W, G, B, K, tau = cfg["dims"], cfg["W"], cfg["G"], cfg["B"], cfg["K"], cfg["tau"]
+    P, ld, x0, host_batches = data
+    x = torch.from_numpy(x0).to(DEV)
+    g = torch.zeros_like(x); m = torch.zeros_like(x)
+    xb = torch.zeros((W, ld), dtype=torch.bfloat16, device=DEV)
+    Z = torch.zeros((G + 1, ld), device=DEV) if tau > 1 else None
+    batches = []
+    for Xb, y in host_batches:
+        Xd = torch.from_numpy(Xb.view(np.int16)).to(DEV).view(torch.bfloat16)
+        batches.append(L.MLPBatch(dims, Xd, torch.from_numpy(y).to(DEV)))
+    pop = L.Population(x, g, G, m=m, z_snapshot=Z, x_bf16=xb, P=P, momentum=0.9, flags=L.WRITE_BF16_SHADOW,
+                       largest_batch=batches[0])
+    eta, lamL, lamG = 0.01, cfg["lamL"], cfg["lamG"]
+
+    def step(t):
+        rl, rg = wl.refresh_masks(t, tau, G, staggered=cfg["staggered"])
+        pop.step(batches[t % K], eta, lamL, lamG, rl, rg)
+
+    secs = _timed_steps(step, steps, warmup)
+    reps = max(10, min(steps, 100))
+    ms_grad = _events_ms(lambda i: pop.grad_loss(batches[i % K]), reps)
+    ms_sel = _events_ms(lambda i: pop.select_leaders(), reps)
+
+    def upd(i):
+        pop.select_leaders(); pop.pull_update(eta, lamL, lamG)
+    ms_pull = _events_ms(upd, reps) - ms_sel
+    flops = float(W) * mlp_flops(dims, B)
+    tf = flops / (ms_grad * 1e-3) / 1e12
+    # traffic the gradient stage cannot avoid: read the bf16 weights once per product that uses them
+    # (forward, d-input) and write the fp32 gradient once
+    wbytes = sum(dims[k] * dims[k + 1] for k in range(len(dims) - 1))
+    min_bytes = float(W) * (2.0 * wbytes * 2 + 4.0 * P)
+    out = {
+        "workload": f"{cfg['name']}, synthetic 10-class Gaussian mixture, W={W} in {G} groups, batch {B}/worker, bf16 operands / "
+                    f"fp32 master, momentum 0.9, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps"
+                    + (" (staggered per group)" if cfg["staggered"] else ""),
+        "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
+        "roofline": {"kernel": "lsgd_grad_loss (MLP): gemm_bf16_kernel launches", "bound": "mfma", "achieved": tf,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None,
+                     "flops_per_launch": flops, "ms_per_launch": ms_grad,
+                     "hbm_floor_ms": min_bytes / (HBM_PEAK_GBS * 1e9) * 1e3},
+        "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
+        "pull_update_GBs": W * 22.0 * P / (ms_pull * 1e-3) / 1e9,
+        "final_mean_loss": float(np.mean(pop.get_losses())),
+    }
+    del pop
+    return out
+
+
+def cpu_mlp(cfg, data, workers):
+    import oracle
+    dims, W, G, B = cfg["dims"], cfg["W"], cfg["G"], cfg["B"]
+    P, ld, x0, host_batches = data
+    Ws = min(workers, W)
+    pop = oracle.Population(x0[:Ws], np.array([0, Ws], dtype=np.int32), momentum=0.9, P=P)
+    reps, t0 = 0, time.perf_counter()
+    while reps < 1 or time.perf_counter() - t0 < 8.0:
+        Xb, y = host_batches[reps % len(host_batches)]
+        pop.grad_loss_mlp(dims, np.ascontiguousarray(Xb[:Ws]), np.ascontiguousarray(y[:Ws]))
+        pop.select(); pop.update(0.01, cfg["lamL"], cfg["lamG"])
+        reps += 1
+    dt = (time.perf_counter() - t0) / reps
+    return {"value": Ws / dt, "unit": "worker-steps/s", "cores": _omp_threads() or os.cpu_count(), "kind": "oracle",
+            "sample": f"{Ws} of the {W} workers (one group), full batch {B} and full model, {reps} whole steps"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c4"])
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -216,6 +314,12 @@ def main():
     if args.workload == "c4":
         primary = stress
         cpu = None if args.no_cpu else cpu_stress()
+    elif args.workload in MLP_CFG:
+        cfg = MLP_CFG[args.workload]
+        data = make_mlp(cfg)
+        line["dtype"] = "bf16"
+        primary = run_mlp(L, args.steps, args.warmup, cfg, data)
+        cpu = None if args.no_cpu else cpu_mlp(cfg, data, cfg["W"] if args.workload == "c3" else 2)
     else:
         data = make_c2()
         primary = run_c2(L, args.steps, args.warmup, data)
