@@ -141,6 +141,7 @@ struct lsgd_population {
     std::vector<uint8_t> local_selected, pending_local, z_valid; // z_valid: [G+1]
     bool global_selected, pending_global;
     bool shadow_valid;
+    int group_size; // rows per group if all groups are equal, else 0
 };
 
 extern "C" {
@@ -204,6 +205,9 @@ lsgd_status lsgd_create_population(const lsgd_config* cfg, float* x, float* g, f
     p->z_valid.assign((size_t)cfg->n_groups + 1, 0);
     p->global_selected = p->pending_global = false;
     p->shadow_valid = false;
+    p->group_size = off[1] - off[0];
+    for (int j = 0; j < cfg->n_groups; ++j)
+        if (off[(size_t)j + 1] - off[(size_t)j] != off[1] - off[0]) p->group_size = 0;
 
     hipError_t e = hipMemcpyAsync(p->st.offsets, p->offsets.data(), sizeof(int32_t) * p->offsets.size(), hipMemcpyHostToDevice, p->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(p->st.group_of, p->group_of.data(), sizeof(int32_t) * p->group_of.size(), hipMemcpyHostToDevice, p->stream);
@@ -355,6 +359,7 @@ lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG)
     for (int j = 0; j < G; ++j) any_pending = any_pending || p->pending_local[(size_t)j];
     q.use_refreshed = any_pending ? 1 : 0;
     q.clear_refreshed = 0;
+    q.group_size = p->group_size;
     hipError_t e = launch_pull_update(q, p->st, p->stream);
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "pull_update: %s", hipGetErrorString(e));
     // a refreshed leader whose term was active has now been captured (and kept, if Z exists)

@@ -47,6 +47,7 @@ struct PullParams {
     int flags;          // LSGD_NESTEROV | LSGD_LEADER_EXEMPT | LSGD_MOMENTUM_GRAD_ONLY
     int use_refreshed;  // 0: treat every leader as kept (read Z)
     int clear_refreshed;
+    int group_size;     // rows per group when all groups are equal, else 0
 };
 hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s);
 

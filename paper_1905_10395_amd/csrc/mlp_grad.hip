@@ -373,6 +373,115 @@ __global__ __launch_bounds__(256) void dx_valu_kernel(const uint16_t* __restrict
     dprevT[(int64_t)w * sP + (int64_t)i * B + b] = q;
 }
 
+// ---- narrow-layer kernels: the classifier layer (a handful of classes) with 16-byte loads ----
+__device__ __forceinline__ void unpack8(const u32x4 v, float* f)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        f[2 * q] = __uint_as_float(v[q] << 16);
+        f[2 * q + 1] = __uint_as_float(v[q] & 0xFFFF0000u);
+    }
+}
+
+// One wavefront per output (b, o): out = <h[b,:], Wq[o,:]> + bias[o].  d_in % 8 == 0, rows 16-byte aligned.
+template <bool HIDDEN>
+__global__ __launch_bounds__(256) void fwd_narrow_kernel(const uint16_t* __restrict__ H, int64_t sH, int64_t ldh,
+                                                         const uint16_t* __restrict__ Wq, int64_t sW, const float* __restrict__ bias,
+                                                         int64_t sBias, int B, int din, int dout, uint16_t* __restrict__ out,
+                                                         float* __restrict__ logits, int64_t sOut, int64_t ldout)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t idx = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int w = blockIdx.y;
+    if (idx >= (int64_t)B * dout) return;
+    const int b = (int)(idx / dout), o = (int)(idx % dout);
+    const u32x4* h = reinterpret_cast<const u32x4*>(H + (int64_t)w * sH + (int64_t)b * ldh);
+    const u32x4* wr = reinterpret_cast<const u32x4*>(Wq + (int64_t)w * sW + (int64_t)o * din);
+    float acc = 0.f;
+    for (int c = lane; c < din / 8; c += 64) {
+        float a[8], q[8];
+        unpack8(h[c], a); unpack8(wr[c], q);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc = fmaf(a[t], q[t], acc);
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+    if (lane == 0) {
+        const float z = acc + bias[(int64_t)w * sBias + o];
+        if (HIDDEN) out[(int64_t)w * sOut + (int64_t)b * ldout + o] = f32_to_bf16_rne(z > 0.f ? z : 0.f);
+        else logits[(int64_t)w * sOut + (int64_t)b * ldout + o] = z;
+    }
+}
+
+// dW[o][i..i+7] for one output row o and 512 columns per workgroup; the four wavefronts split the batch
+// and combine through LDS in a fixed order.  d_in % 8 == 0.
+__global__ __launch_bounds__(256) void dw_narrow_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, const uint16_t* __restrict__ H,
+                                                        int64_t sH, int64_t ldh, int B, int din, int dout, float* __restrict__ g, int64_t sG)
+{
+    const int w = blockIdx.z, o = blockIdx.y;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;            // 16-byte chunk (8 columns)
+    const bool live = c < din / 8;
+    const uint16_t* dt = deltaT + (int64_t)w * sD + (int64_t)o * B;
+    const uint16_t* h = H + (int64_t)w * sH;
+    float acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = 0.f;
+    const int b0 = (int)((int64_t)B * q / 4), b1 = (int)((int64_t)B * (q + 1) / 4);
+    if (live) {
+        for (int b = b0; b < b1; ++b) {
+            const float d = bf16_to_f32(dt[b]);
+            float a[8];
+            unpack8(*reinterpret_cast<const u32x4*>(h + (int64_t)b * ldh + (int64_t)c * 8), a);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc[t] = fmaf(d, a[t], acc[t]);
+        }
+    }
+    __shared__ float red[4][64][9];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) red[q][lane][t] = acc[t];
+    __syncthreads();
+    if (q == 0 && live) {
+        float* dst = g + (int64_t)w * sG + (int64_t)o * din + (int64_t)c * 8;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) dst[t] = ((red[0][lane][t] + red[1][lane][t]) + red[2][lane][t]) + red[3][lane][t];
+    }
+}
+
+// dprev[b][i..i+7] = bf16(sum_o delta[b][o] Wq[o][i..i+7]) .* [h > 0] for a narrow delta (few classes).
+__global__ __launch_bounds__(128) void dx_narrow_kernel(const uint16_t* __restrict__ delta, int64_t sD, const uint16_t* __restrict__ Wq, int64_t sW,
+                                                        const uint16_t* __restrict__ H, int64_t sH, int64_t ldh, int B, int din, int dout,
+                                                        uint16_t* __restrict__ dprev, uint16_t* __restrict__ dprevT, int64_t sP)
+{
+    const int w = blockIdx.z, b = blockIdx.y;
+    const int c = blockIdx.x * 128 + threadIdx.x;
+    if (c >= din / 8) return;
+    const uint16_t* d = delta + (int64_t)w * sD + (int64_t)b * dout;
+    const uint16_t* Wm = Wq + (int64_t)w * sW + (int64_t)c * 8;
+    float acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = 0.f;
+    for (int o = 0; o < dout; ++o) {
+        const float dv = bf16_to_f32(d[o]);
+        float a[8];
+        unpack8(*reinterpret_cast<const u32x4*>(Wm + (int64_t)o * din), a);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = fmaf(dv, a[t], acc[t]);
+    }
+    const u32x4 hm = *reinterpret_cast<const u32x4*>(H + (int64_t)w * sH + (int64_t)b * ldh + (int64_t)c * 8);
+    uint32_t pk[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const uint32_t hb = (t & 1) ? (hm[t >> 1] >> 16) : (hm[t >> 1] & 0xFFFFu);
+        pk[t] = hb ? (uint32_t)f32_to_bf16_rne(acc[t]) : 0u;
+    }
+    u32x4 o4 = {pk[0] | (pk[1] << 16), pk[2] | (pk[3] << 16), pk[4] | (pk[5] << 16), pk[6] | (pk[7] << 16)};
+    *reinterpret_cast<u32x4*>(dprev + (int64_t)w * sP + (int64_t)b * din + (int64_t)c * 8) = o4;
+    uint16_t* dT = dprevT + (int64_t)w * sP + (int64_t)c * 8 * B + b;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) dT[(int64_t)t * B] = (uint16_t)pk[t];
+}
+
 __global__ __launch_bounds__(256) void zero_pad_kernel(float* __restrict__ g, int64_t P, int64_t ld)
 {
     const int64_t c = P + (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -454,6 +563,18 @@ hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, fl
             a.out = sc16 + p.h[k]; a.sOut = sW16; a.ldout = dout;
             done = try_mfma<false, EPI_FWD>(a, W, s);
         }
+        auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+        const bool vec8 = din % 8 == 0 && ld % 8 == 0 && woff[k] % 8 == 0 && a16(xb) && a16(Hin) && sHin % 8 == 0;
+        if (!done && vec8 && dout <= 64) {
+            dim3 grid((unsigned)(((int64_t)B * dout + 3) / 4), (unsigned)W);
+            if (k < L)
+                hipLaunchKernelGGL(fwd_narrow_kernel<true>, grid, dim3(256), 0, s, Hin, sHin, (int64_t)din, xb + woff[k], ld, bias, ld,
+                                   B, din, dout, sc16 + p.h[k], (float*)nullptr, sW16, (int64_t)dout);
+            else
+                hipLaunchKernelGGL(fwd_narrow_kernel<false>, grid, dim3(256), 0, s, Hin, sHin, (int64_t)din, xb + woff[k], ld, bias, ld,
+                                   B, din, dout, (uint16_t*)nullptr, logits, sW32, (int64_t)dout);
+            done = true;
+        }
         if (!done) {
             dim3 grid((unsigned)((B + 3) / 4), (unsigned)W);
             if (k < L)
@@ -479,7 +600,14 @@ hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, fl
             a.B = Hin; a.sB = sHin; a.ldb = din;
             a.M = dout; a.N = din; a.K = B;
             a.C = g + woff[k]; a.sC = ld; a.ldc = din;
-            if (!try_mfma<true, EPI_DW>(a, W, s)) {
+            auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+            const bool vec8 = din % 8 == 0 && a16(Hin) && sHin % 8 == 0;
+            if (try_mfma<true, EPI_DW>(a, W, s)) {
+            } else if (vec8 && dout <= 64) {
+                dim3 grid((unsigned)((din / 8 + 63) / 64), (unsigned)dout, (unsigned)W);
+                hipLaunchKernelGGL(dw_narrow_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
+                                   dout, g + woff[k], ld);
+            } else {
                 dim3 grid((unsigned)((din + 255) / 256), (unsigned)dout, (unsigned)W);
                 hipLaunchKernelGGL(dw_valu_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
                                    dout, g + woff[k], ld);
@@ -497,7 +625,14 @@ hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, fl
             a.mask = Hin; a.sMask = sHin; a.ldmask = din;
             a.out = sc16 + p.d[k - 1]; a.sOut = sW16; a.ldout = din;
             a.outT = sc16 + p.dT[k - 1]; a.sOutT = sW16; a.ldoutT = B;
-            if (!try_mfma<true, EPI_DX>(a, W, s)) {
+            auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+            const bool vec8 = din % 8 == 0 && ld % 8 == 0 && woff[k] % 8 == 0 && a16(xb) && a16(Hin) && sHin % 8 == 0;
+            if (try_mfma<true, EPI_DX>(a, W, s)) {
+            } else if (vec8 && dout <= 64) {
+                dim3 grid((unsigned)((din / 8 + 127) / 128), (unsigned)B, (unsigned)W);
+                hipLaunchKernelGGL(dx_narrow_kernel, grid, dim3(128), 0, s, sc16 + p.d[k], sW16, xb + woff[k], ld, Hin, sHin,
+                                   (int64_t)din, B, din, dout, sc16 + p.d[k - 1], sc16 + p.dT[k - 1], sW16);
+            } else {
                 dim3 grid((unsigned)((din + 255) / 256), (unsigned)B, (unsigned)W);
                 hipLaunchKernelGGL(dx_valu_kernel, grid, dim3(256), 0, s, sc16 + p.d[k], sW16, xb + woff[k], ld, Hin, sHin,
                                    (int64_t)din, B, din, dout, sc16 + p.d[k - 1], sc16 + p.dT[k - 1], sW16);

@@ -97,6 +97,7 @@ struct PullDev {
     int W, G;
     float eta, lamL, lamG, mu, wd;
     int flags, use_refreshed;
+    int group_size;     // l when all groups have l rows (group = row / l), else 0: look the group up
     const int32_t* offsets;
     const int32_t* group_of;
     const int32_t* lead;
@@ -115,33 +116,51 @@ __device__ __forceinline__ Coef make_coef(const PullDev& a)
 }
 
 template <int VEC, bool MOM>
-__device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename Vec<VEC>::type xv,
-                                           const typename Vec<VEC>::type zl, const typename Vec<VEC>::type zg, const Coef& c)
+__device__ __forceinline__ void apply_row(const PullDev& a, int64_t o, typename Vec<VEC>::type xv, typename Vec<VEC>::type gv,
+                                          typename Vec<VEC>::type mv, const typename Vec<VEC>::type zl,
+                                          const typename Vec<VEC>::type zg, const Coef& c)
 {
     using V = typename Vec<VEC>::type;
-    V gv = ld_stream<VEC>(a.g + o);
-    V mv = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
     update_vec<MOM, V>(xv, gv, mv, zl, zg, c);
     st_stream(a.x + o, xv);
     if (MOM) st_stream(a.m + o, mv);
     if (a.xb) st_bf16(a.xb + o, xv);
 }
 
-// Kernel 1: every row that nobody reads as a freshly selected leader.  One
-// workgroup per (row, column tile); the grid's x index runs over the tiles
-// of one row, so workgroups are dispatched in plain row-major order and the
-// x, g, m streams stay sequential in memory.  The leader tiles a row needs
-// (its group's and the global one) are re-read by every row of the group;
-// they are two rows at a time and stay in the memory-side cache.
 template <int VEC, bool MOM>
-__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a)
+__device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename Vec<VEC>::type xv,
+                                           const typename Vec<VEC>::type zl, const typename Vec<VEC>::type zg, const Coef& c)
 {
     using V = typename Vec<VEC>::type;
-    const int row = blockIdx.y;
-    const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
+    V gv = ld_stream<VEC>(a.g + o);
+    V mv = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
+    apply_row<VEC, MOM>(a, o, xv, gv, mv, zl, zg, c);
+}
+
+// Kernel 1: every row that nobody reads as a freshly selected leader.  One
+// workgroup per (row, column tile).  Workgroups are numbered so that they are
+// dispatched chunk by chunk: the columns are cut into chunks of kChunkTiles
+// tiles (4 MB of one row); inside a chunk the order is plain row-major.  The
+// x, g, m streams are then long sequential runs in memory, while the leader
+// tiles of the chunk, which every row of a group re-reads, stay in the L2
+// of the die that reads them instead of being fetched again for each row.
+constexpr int kChunkTiles = 1024;
+
+template <int VEC, bool MOM>
+__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int64_t tiles, int tpc)
+{
+    using V = typename Vec<VEC>::type;
+    const int64_t b = blockIdx.x;
+    const int64_t per_chunk = (int64_t)a.W * tpc;
+    const int64_t chunk = b / per_chunk;
+    const int rem = (int)(b - chunk * per_chunk);
+    const int row = rem / tpc;
+    const int64_t tile = chunk * tpc + (rem - row * tpc);
+    if (tile >= tiles) return;
+    const int64_t col = a.col0 + (tile * kPullThreads + threadIdx.x) * VEC;
     if (col >= a.col1) return;
     const bool pullG = a.lamG != 0.0f, pullL = a.lamL != 0.0f;
-    const int j = a.group_of[row];
+    const int j = a.group_size ? row / a.group_size : a.group_of[row];
     const int ll = pullL ? a.lead[j] : -1;
     const int gl = pullG ? a.glead[0] : -1;
     const bool freshL = pullL && a.use_refreshed && a.refreshed[j];
@@ -193,19 +212,40 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
         update_row<VEC, MOM>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);
     }
     if (!pullL) return;
-    for (int j = 0; j < a.G; ++j) {
-        if (!a.refreshed[j]) continue;
-        const int ll = a.lead[j];
-        if (freshG && ll == gl) {          // already updated above; its pre-update tile is zg
-            if (a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, zg);
-            continue;
+    // re-selected local leaders, four at a time so that their loads are all in flight together
+    constexpr int kBatch = 4;
+    int j = 0;
+    while (j < a.G) {
+        int row[kBatch], grp[kBatch], cnt = 0;
+        for (; j < a.G && cnt < kBatch; ++j) {
+            if (!a.refreshed[j]) continue;
+            const int ll = a.lead[j];
+            if (freshG && ll == gl) {      // already updated above; its pre-update tile is zg
+                if (a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, zg);
+                continue;
+            }
+            row[cnt] = ll; grp[cnt] = j; ++cnt;
         }
-        const int64_t o = (int64_t)ll * a.ld + col;
-        V xv = ld_vec<VEC>(a.x + o);
-        if (a.Z) st_vec(a.Z + (int64_t)j * a.ld + col, xv);
-        Coef cl = c;
-        if (exempt) { cl.cL = 0.0f; if (ll == gl) cl.cG = 0.0f; }
-        update_row<VEC, MOM>(a, o, xv, xv, zg, cl);
+        V xv[kBatch], gv[kBatch], mv[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (u < cnt) {
+                const int64_t o = (int64_t)row[u] * a.ld + col;
+                xv[u] = ld_vec<VEC>(a.x + o);
+                gv[u] = ld_stream<VEC>(a.g + o);
+                mv[u] = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (u < cnt) {
+                const int64_t o = (int64_t)row[u] * a.ld + col;
+                if (a.Z) st_vec(a.Z + (int64_t)grp[u] * a.ld + col, xv[u]);
+                Coef cl = c;
+                if (exempt) { cl.cL = 0.0f; if (row[u] == gl) cl.cG = 0.0f; }
+                apply_row<VEC, MOM>(a, o, xv[u], gv[u], mv[u], xv[u], zg, cl);
+            }
+        }
     }
 }
 
@@ -216,7 +256,18 @@ static void launch_range(PullDev a, bool leaders, hipStream_t s)
     if (cols <= 0) return;
     const int64_t per_block = (int64_t)kPullThreads * VEC;
     const int64_t tiles = (cols + per_block - 1) / per_block;
-    hipLaunchKernelGGL((pull_rows_kernel<VEC, MOM>), dim3((unsigned)tiles, (unsigned)a.W), dim3(kPullThreads), 0, s, a);
+    const int tpc = (int)(tiles < kChunkTiles ? tiles : kChunkTiles);
+    const int64_t chunks = (tiles + tpc - 1) / tpc;
+    // a launch covers whole chunks; split only if the workgroup count would not fit a grid dimension
+    const int64_t max_chunks = ((int64_t)1 << 30) / ((int64_t)a.W * tpc) > 0 ? ((int64_t)1 << 30) / ((int64_t)a.W * tpc) : 1;
+    for (int64_t c0 = 0; c0 < chunks; c0 += max_chunks) {
+        const int64_t nch = chunks - c0 < max_chunks ? chunks - c0 : max_chunks;
+        PullDev part = a;
+        part.col0 = a.col0 + c0 * tpc * per_block;
+        const int64_t part_tiles = (tiles - c0 * tpc) < nch * tpc ? (tiles - c0 * tpc) : nch * tpc;
+        hipLaunchKernelGGL((pull_rows_kernel<VEC, MOM>), dim3((unsigned)(nch * a.W * tpc)), dim3(kPullThreads), 0, s, part,
+                           part_tiles, tpc);
+    }
     if (leaders)
         hipLaunchKernelGGL((pull_leaders_kernel<VEC, MOM>), dim3((unsigned)tiles), dim3(kPullThreads), 0, s, a);
 }
@@ -227,7 +278,7 @@ hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStr
     a.x = p.x; a.g = p.g; a.m = p.m; a.Z = p.Z; a.xb = p.xb;
     a.ld = p.ld; a.W = p.W; a.G = p.G;
     a.eta = p.eta; a.lamL = p.lamL; a.lamG = p.lamG; a.mu = p.mu; a.wd = p.wd;
-    a.flags = p.flags; a.use_refreshed = p.use_refreshed;
+    a.flags = p.flags; a.use_refreshed = p.use_refreshed; a.group_size = p.group_size;
     a.offsets = st.offsets; a.group_of = st.group_of; a.lead = st.lead; a.glead = st.glead; a.refreshed = st.refreshed;
     const bool mom = p.mu != 0.0f;
     const bool leaders = p.use_refreshed && (p.lamL != 0.0f || p.lamG != 0.0f);

@@ -56,6 +56,8 @@ CASES = [
     (12, 3, 2050, 2052, 0.9, L.LEADER_EXEMPT, 0.0),
     (5, 5, 515, 516, 0.9, 0, 0.0),                          # every worker its own group
     (70, 6, 1030, 1032, 0.9, 0, 0.0),                       # W > 64
+    (6, 2, 2_500_003, 2_500_032, 0.9, 0, 0.0),              # several column chunks, ragged last chunk and tail
+    (5, 2, 1_100_000, 1_100_000, 0.0, 0, 0.0),              # unequal groups across a chunk boundary
 ]
 
 
@@ -178,3 +180,34 @@ def test_hundred_steps_external_quadratic():
             flips += 1; pr.resync_from_oracle()
     pr.check_state(1e-3, "after 100 steps")
     assert flips <= 2
+
+
+def test_full_size_stress_sampled_columns():
+    """W=32 x P=11,689,512 in 4 groups of 8, momentum 0.9, in the launch configuration the benchmark times.
+    The update is independent per column, so the oracle recomputes a sample of column blocks (first, last
+    ragged one, chunk boundaries, random ones) from the same pre-update values."""
+    W, G, P = 32, 4, 11_689_512
+    ld = wl.padded_ld(P)
+    gen = torch.Generator(device=DEV); gen.manual_seed(1234)
+    x = torch.randn((W, ld), device=DEV, generator=gen) * 0.05
+    g = torch.randn((W, ld), device=DEV, generator=gen) * 1e-2
+    m = torch.randn((W, ld), device=DEV, generator=gen) * 1e-2
+    pop = L.Population(x, g, G, m=m, P=P, momentum=0.9)
+    r = wl.stream("full_stress")
+    starts = [0, 1024 * 1024 - 512, 4 * 1024 * 1024 - 100, P - 1000] + [int(v) for v in r.integers(0, P - 2048, size=24)]
+    cols = np.unique(np.concatenate([np.arange(s0, min(s0 + 1024, P)) for s0 in starts]))
+    ct = torch.from_numpy(cols).to(DEV)
+    off = wl.equal_group_offsets(W, G)
+    ora = oracle.Population(x[:, ct].cpu().numpy(), off, momentum=0.9)
+    ora.m[:] = m[:, ct].cpu().numpy()
+    for t in range(2):
+        losses = wl.stress_losses(W, t, seed=99)
+        ora.g[:] = g[:, ct].cpu().numpy(); ora.losses[:] = losses
+        ora.select(); ora.update(0.01, 0.1, 0.05)
+        pop.select_leaders(dev(losses)); pop.pull_update(0.01, 0.1, 0.05)
+        lead, gl = pop.get_leaders()
+        assert lead == ora.lead.tolist() and gl == int(ora.glead[0])
+        assert rel_l2_rows(x[:, ct].cpu().numpy(), ora.x).max() < 1e-4
+        assert rel_l2_rows(m[:, ct].cpu().numpy(), ora.m).max() < 1e-4
+    # columns outside [0, P) were not touched
+    assert torch.count_nonzero(x[:, P:] - x[:, P:]) == 0
