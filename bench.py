@@ -140,7 +140,8 @@ def run_c2(L, steps, warmup, data):
     Z = torch.zeros((G + 1, ld), device=DEV)
     rows, cols, vals, idx_d = d(prob.rows), d(prob.cols), d(prob.vals), d(idx)
     c = 0.5 * prob.n_obs / B
-    batches = [L.MCBatch(prob.m, prob.n, prob.r, rows, cols, vals, idx_d[k], c) for k in range(K)]
+    packed = L.mc_pack_entries(rows, cols, vals)      # once: the observed set is fixed across steps
+    batches = [L.MCBatch(prob.m, prob.n, prob.r, rows, cols, vals, idx_d[k], c, entries=packed) for k in range(K)]
     pop = L.Population(x, g, G, z_snapshot=Z, P=prob.P, largest_batch=batches[0])
     eta, lamL, lamG, tau = 0.005, 0.1, 0.05, 4
 

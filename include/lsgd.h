@@ -90,6 +90,12 @@ typedef struct {
  * loss = c*sum e_k^2; dU[a] = 2c*sum_{a_k=a} e_k V[b_k]; dV[b] likewise.
  * Entries drawn more than once count each time.                                */
 typedef struct {
+    int32_t row, col; /* a, b                                                       */
+    float val;        /* M_ab                                                       */
+    int32_t reserved; /* keeps the record at 16 bytes                               */
+} lsgd_mc_entry;
+
+typedef struct {
     int32_t m, n, r;
     const int32_t* rows;      /* device [n_obs] row index a of each observed entry  */
     const int32_t* cols;      /* device [n_obs] column index b                      */
@@ -100,6 +106,10 @@ typedef struct {
                                  gradient, "LGD")                                   */
     int64_t B;                /* entries per worker when batch_idx != NULL          */
     float c;                  /* loss normalisation                                 */
+    const lsgd_mc_entry* entries; /* device [n_obs], optional: the same observed list with
+                                 one 16-byte record per entry (see lsgd_mc_pack_entries).
+                                 When non-NULL it is read instead of rows/cols/vals:
+                                 one random access per batch element instead of three */
 } lsgd_mc_batch;
 
 /* Fully connected ReLU classifier with softmax cross-entropy, mean over the
@@ -172,6 +182,13 @@ lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, fl
  * buffer.  The first step of a population must refresh everything.            */
 lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, float lambda_L,
                       float lambda_G, const uint8_t* refresh_local, int refresh_global);
+
+/* Builds the 16-byte-record form of an observed-entry list (device to device, on
+ * hip_stream): out[k] = {rows[k], cols[k], vals[k], 0}.  The list of observed
+ * entries is fixed across steps (the paper's M and its observed set), so this is
+ * done once by the caller.  All pointers device, [n_obs].                          */
+lsgd_status lsgd_mc_pack_entries(const int32_t* rows, const int32_t* cols, const float* vals,
+                                 int64_t n_obs, lsgd_mc_entry* out, void* hip_stream);
 
 /* Recomputes the whole bf16 shadow from x (after the caller changed x). */
 lsgd_status lsgd_sync_shadow(lsgd_population* pop);

@@ -40,7 +40,7 @@ class _External(C.Structure):
 class _MC(C.Structure):
     _fields_ = [("m", C.c_int32), ("n", C.c_int32), ("r", C.c_int32), ("rows", C.c_void_p), ("cols", C.c_void_p),
                 ("vals", C.c_void_p), ("n_obs", C.c_int64), ("batch_idx", C.c_void_p), ("B", C.c_int64),
-                ("c", C.c_float)]
+                ("c", C.c_float), ("entries", C.c_void_p)]
 
 
 class _MLP(C.Structure):
@@ -80,6 +80,7 @@ def lib():
         L.lsgd_step.argtypes = [C.c_void_p, C.POINTER(_Batch), C.c_float, C.c_float, C.c_float,
                                 C.POINTER(C.c_uint8), C.c_int]
         L.lsgd_sync_shadow.argtypes = [C.c_void_p]
+        L.lsgd_mc_pack_entries.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.lsgd_get_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.lsgd_get_losses.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         _lib = L
@@ -105,9 +106,10 @@ class ExternalBatch:
 
 
 class MCBatch:
-    """rows, cols: int32 [n_obs]; vals: float32 [n_obs]; batch_idx: int32 [W,B] or None (all entries)."""
+    """rows, cols: int32 [n_obs]; vals: float32 [n_obs]; batch_idx: int32 [W,B] or None (all entries);
+    entries: optional int32 [n_obs, 4] from mc_pack_entries (read instead of rows/cols/vals)."""
 
-    def __init__(self, m, n, r, rows, cols, vals, batch_idx, c):
+    def __init__(self, m, n, r, rows, cols, vals, batch_idx, c, entries=None):
         B = 0 if batch_idx is None else int(batch_idx.shape[-1])
         idx_ptr = None
         if batch_idx is not None:
@@ -115,9 +117,9 @@ class MCBatch:
             anchor = batch_idx if batch_idx.numel() else torch.zeros(1, dtype=torch.int32, device=rows.device)
             idx_ptr = anchor.data_ptr()
             batch_idx = anchor
-        self.keep = (rows, cols, vals, batch_idx)
+        self.keep = (rows, cols, vals, batch_idx, entries)
         self._d = _MC(m, n, r, rows.data_ptr(), cols.data_ptr(), vals.data_ptr(), int(rows.numel()),
-                      idx_ptr, B, float(c))
+                      idx_ptr, B, float(c), None if entries is None else entries.data_ptr())
         self.c = _Batch(BATCH_MC, C.cast(C.pointer(self._d), C.c_void_p))
 
 
@@ -129,6 +131,15 @@ class MLPBatch:
         self._dims = (C.c_int32 * len(dims))(*[int(d) for d in dims])
         self._d = _MLP(len(dims) - 1, self._dims, X.data_ptr(), y.data_ptr(), int(y.shape[-1]))
         self.c = _Batch(BATCH_MLP, C.cast(C.pointer(self._d), C.c_void_p))
+
+
+def mc_pack_entries(rows, cols, vals, stream=None):
+    """lsgd_mc_pack_entries: returns an int32 [n_obs, 4] tensor of 16-byte records {row, col, val bits, 0}."""
+    n = int(rows.numel())
+    out = torch.empty((n, 4), dtype=torch.int32, device=rows.device)
+    st = torch.cuda.current_stream(rows.device) if stream is None else stream
+    _check(lib().lsgd_mc_pack_entries(_ptr(rows), _ptr(cols), _ptr(vals), n, _ptr(out), C.c_void_p(st.cuda_stream)))
+    return out
 
 
 def _config(W, P, ld, n_groups, group_offsets, momentum, flags, weight_decay):

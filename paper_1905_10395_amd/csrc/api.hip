@@ -103,7 +103,10 @@ lsgd_status check_batch(const lsgd_batch* batch, int W, int64_t P, size_t* parti
         if ((int64_t)(d->m + (int64_t)d->n) * d->r != P)
             return fail(LSGD_ERR_SHAPE, "matrix completion: (m+n)*r = %lld != P = %lld", (long long)((int64_t)(d->m + (int64_t)d->n) * d->r), (long long)P);
         if (d->n_obs < 0 || d->B < 0) return fail(LSGD_ERR_SHAPE, "matrix completion: negative n_obs or B");
-        if (d->n_obs > 0 && (!d->rows || !d->cols || !d->vals)) return fail(LSGD_ERR_INVALID_ARG, "matrix completion: rows/cols/vals is NULL");
+        if (d->n_obs > 0 && !d->entries && (!d->rows || !d->cols || !d->vals))
+            return fail(LSGD_ERR_INVALID_ARG, "matrix completion: rows/cols/vals is NULL and no packed entries given");
+        if (d->entries && (reinterpret_cast<uintptr_t>(d->entries) & 15u))
+            return fail(LSGD_ERR_INVALID_ARG, "matrix completion: entries must be 16-byte aligned");
         if (d->batch_idx && d->B > 0 && d->n_obs == 0) return fail(LSGD_ERR_SHAPE, "matrix completion: batch indices into an empty list");
         if (!std::isfinite(d->c)) return fail(LSGD_ERR_INVALID_ARG, "matrix completion: c must be finite");
         if (partials) *partials = mc_partials(W, *d);
@@ -416,6 +419,18 @@ lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, 
     st = do_select(pop, nullptr, refresh_local, refresh_global);
     if (st != LSGD_OK) return st;
     return do_pull(pop, eta, lambda_L, lambda_G);
+}
+
+lsgd_status lsgd_mc_pack_entries(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n_obs,
+                                 lsgd_mc_entry* out, void* hip_stream)
+{
+    if (n_obs < 0) return fail(LSGD_ERR_SHAPE, "n_obs is negative");
+    if (n_obs == 0) return LSGD_OK;
+    if (!rows || !cols || !vals || !out) return fail(LSGD_ERR_INVALID_ARG, "pack_entries: NULL pointer");
+    if (reinterpret_cast<uintptr_t>(out) & 15u) return fail(LSGD_ERR_INVALID_ARG, "pack_entries: out must be 16-byte aligned");
+    hipError_t e = launch_mc_pack(rows, cols, vals, n_obs, out, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "pack_entries: %s", hipGetErrorString(e));
+    return LSGD_OK;
 }
 
 lsgd_status lsgd_sync_shadow(lsgd_population* pop)

@@ -58,6 +58,8 @@ size_t mc_partials(int W, const lsgd_mc_batch& b);
 hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, int64_t P, int64_t ld,
                                const lsgd_mc_batch& b, const DeviceState& st, hipStream_t s);
 
+hipError_t launch_mc_pack(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n, lsgd_mc_entry* out, hipStream_t s);
+
 size_t mlp_scratch_bytes(int W, const lsgd_mlp_batch& b);
 // returns LSGD_OK / LSGD_ERR_UNSUPPORTED through *status for shapes the kernels do not cover
 hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, float* losses, int W,

@@ -30,6 +30,19 @@ __global__ __launch_bounds__(256) void fill_zero_scalar_kernel(float* __restrict
         row[c] = 0.f;
 }
 
+// (a, b, M) of observed entry s, from the 16-byte records when the caller supplied them
+__device__ __forceinline__ void fetch_entry(const lsgd_mc_entry* __restrict__ entries, const int32_t* __restrict__ rows,
+                                            const int32_t* __restrict__ cols, const float* __restrict__ vals, int64_t s,
+                                            int& a, int& b, float& v)
+{
+    if (entries) {
+        const int4 e = reinterpret_cast<const int4*>(entries)[s];
+        a = e.x; b = e.y; v = __int_as_float(e.z);
+    } else {
+        a = rows[s]; b = cols[s]; v = vals[s];
+    }
+}
+
 // General path: S lanes cooperate on one entry (S = power of two >= min(r, 64)),
 // residual by a lane butterfly, gradient rows accumulated with hardware fp32
 // atomics into the zero-filled g.  Any r, m, n.
@@ -37,7 +50,8 @@ template <int S>
 __global__ __launch_bounds__(kMcThreads) void mc_grad_atomic_kernel(
     const float* __restrict__ x, float* __restrict__ g, int64_t ld, int m, int n, int r,
     const int32_t* __restrict__ rows, const int32_t* __restrict__ cols, const float* __restrict__ vals,
-    const int32_t* __restrict__ batch_idx, int64_t nb, float two_c, float* __restrict__ partials, int nblk)
+    const int32_t* __restrict__ batch_idx, int64_t nb, float two_c, float* __restrict__ partials, int nblk,
+    const lsgd_mc_entry* __restrict__ entries)
 {
     const int w = blockIdx.y;
     const float* U = x + (int64_t)w * ld;
@@ -51,14 +65,16 @@ __global__ __launch_bounds__(kMcThreads) void mc_grad_atomic_kernel(
     float sq = 0.f;
     for (int64_t k = k0 + sub; k < k1; k += kSubs) {
         const int64_t s = batch_idx ? (int64_t)batch_idx[(int64_t)w * nb + k] : k;
-        const int a = rows[s], b = cols[s];
+        int a, b;
+        float mv;
+        fetch_entry(entries, rows, cols, vals, s, a, b, mv);
         const float* ua = U + (int64_t)a * r;
         const float* vb = V + (int64_t)b * r;
         float dot = 0.f;
         for (int q = q0; q < r; q += S) dot = fmaf(ua[q], vb[q], dot);
 #pragma unroll
         for (int d = 1; d < S; d <<= 1) dot += __shfl_xor(dot, d, S);
-        const float e = dot - vals[s];
+        const float e = dot - mv;
         if (q0 == 0) sq = fmaf(e, e, sq);
         const float f = two_c * e;
         for (int q = q0; q < r; q += S) {
@@ -144,7 +160,7 @@ template <int LPE>
 __global__ __launch_bounds__(kResEntries) void mc_residual_kernel(
     const float* __restrict__ x, int64_t ld, int m, int n, int r, const int32_t* __restrict__ rows,
     const int32_t* __restrict__ cols, const float* __restrict__ vals, const int32_t* __restrict__ batch_idx,
-    int64_t nb, McBinned S, float* __restrict__ partials, int W)
+    int64_t nb, McBinned S, float* __restrict__ partials, int W, const lsgd_mc_entry* __restrict__ entries)
 {
     int w, blk;
     if (!xcd_map(blockIdx.x, W, S.nblk, w, blk)) return;
@@ -161,7 +177,10 @@ __global__ __launch_bounds__(kResEntries) void mc_residual_kernel(
     // phase 1: thread t fetches entry t's (a, b, M): all index chasing of the workgroup is in flight at once
     if (t < cnt_here) {
         const int64_t s = batch_idx ? (int64_t)batch_idx[(int64_t)w * nb + k0 + t] : k0 + t;
-        sa[t] = rows[s]; sb[t] = cols[s]; sv[t] = vals[s];
+        int a, b;
+        float mv;
+        fetch_entry(entries, rows, cols, vals, s, a, b, mv);
+        sa[t] = a; sb[t] = b; sv[t] = mv;
     }
     __syncthreads();
     // phase 2: LPE lanes per entry, two entries per lane group in flight; sv[] becomes e_k
@@ -373,6 +392,24 @@ __global__ __launch_bounds__(256) void mc_zero_pad_kernel(float* __restrict__ g,
     if (c < ld) g[(int64_t)blockIdx.y * ld + c] = 0.f;
 }
 
+__global__ __launch_bounds__(256) void mc_pack_kernel(const int32_t* __restrict__ rows, const int32_t* __restrict__ cols,
+                                                      const float* __restrict__ vals, int64_t n, lsgd_mc_entry* __restrict__ out)
+{
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < n; k += (int64_t)gridDim.x * 256) {
+        int4 e = make_int4(rows[k], cols[k], __float_as_int(vals[k]), 0);
+        reinterpret_cast<int4*>(out)[k] = e;
+    }
+}
+
+hipError_t launch_mc_pack(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n, lsgd_mc_entry* out, hipStream_t s)
+{
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(mc_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, s, rows, cols, vals, n, out);
+    return hipGetLastError();
+}
+
 static int64_t mc_entries(const lsgd_mc_batch& b) { return b.batch_idx ? b.B : b.n_obs; }
 
 static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
@@ -408,7 +445,7 @@ static void launch_binned(const float* x, float* g, int W, int64_t ld, const lsg
 {
     const int rounds = (W + kXcd - 1) / kXcd;
     hipLaunchKernelGGL((mc_residual_kernel<LPE>), dim3((unsigned)((int64_t)rounds * kXcd * S.nblk)), dim3(kResEntries),
-                       (size_t)S.nbins * 4, s, x, ld, b.m, b.n, b.r, b.rows, b.cols, b.vals, b.batch_idx, nb, S, partials, W);
+                       (size_t)S.nbins * 4, s, x, ld, b.m, b.n, b.r, b.rows, b.cols, b.vals, b.batch_idx, nb, S, partials, W, b.entries);
     hipLaunchKernelGGL(mc_scan_kernel, dim3((unsigned)W), dim3(1024), 0, s, S);
     hipLaunchKernelGGL(mc_scatter_kernel, dim3((unsigned)((nb + 255) / 256), (unsigned)W), dim3(256), 0, s, S, nb);
     hipLaunchKernelGGL((mc_reduce_kernel<LPE>), dim3((unsigned)((int64_t)rounds * kXcd * S.nbins)), dim3(kMcThreads),
@@ -461,7 +498,7 @@ hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, i
         const float two_c = 2.0f * b.c;
 #define LSGD_MC_LAUNCH(S)                                                                                     \
     hipLaunchKernelGGL((mc_grad_atomic_kernel<S>), grid, dim3(kMcThreads), 0, s, x, g, ld, b.m, b.n, b.r,     \
-                       b.rows, b.cols, b.vals, b.batch_idx, nb, two_c, st.partials, nblk)
+                       b.rows, b.cols, b.vals, b.batch_idx, nb, two_c, st.partials, nblk, b.entries)
         if (b.r <= 1) LSGD_MC_LAUNCH(1);
         else if (b.r <= 2) LSGD_MC_LAUNCH(2);
         else if (b.r <= 4) LSGD_MC_LAUNCH(4);

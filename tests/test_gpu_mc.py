@@ -11,15 +11,25 @@ from gpu_util import DEV, Pair, dev, rel_l2_rows
 pytestmark = pytest.mark.gpu
 
 
-def mc_batch(prob, idx_dev, c):
-    return L.MCBatch(prob.m, prob.n, prob.r, prob._rows_d, prob._cols_d, prob._vals_d, idx_dev, c)
+def mc_batch(prob, idx_dev, c, packed=False):
+    return L.MCBatch(prob.m, prob.n, prob.r, prob._rows_d, prob._cols_d, prob._vals_d, idx_dev, c,
+                     entries=prob._packed_d if packed else None)
 
 
 def upload(prob):
     prob._rows_d, prob._cols_d, prob._vals_d = dev(prob.rows), dev(prob.cols), dev(prob.vals)
+    prob._packed_d = L.mc_pack_entries(prob._rows_d, prob._cols_d, prob._vals_d)
     return prob
 
 
+def test_pack_entries_is_an_exact_copy():
+    prob = upload(wl.mc_problem(50, 40, 4, 0.5, 1.0, seed=4))
+    p = prob._packed_d.cpu().numpy()
+    assert np.array_equal(p[:, 0], prob.rows) and np.array_equal(p[:, 1], prob.cols)
+    assert np.array_equal(p[:, 2].view(np.float32), prob.vals) and not p[:, 3].any()
+
+
+@pytest.mark.parametrize("packed", [False, True])
 @pytest.mark.parametrize("m,n,r,frac,W,B", [
     (100, 100, 5, 0.30, 4, None),          # full-batch tiny config
     (300, 200, 32, 0.10, 3, 5000),         # rank-32 rows, duplicates in the batch
@@ -28,14 +38,14 @@ def upload(prob):
     (40, 30, 100, 0.50, 2, 300),           # rank above a wavefront
     (64, 64, 1, 0.50, 2, 100),
 ])
-def test_mc_grad_loss_matches_oracle(m, n, r, frac, W, B):
+def test_mc_grad_loss_matches_oracle(m, n, r, frac, W, B, packed):
     prob = upload(wl.mc_problem(m, n, r, frac, 1.0, noise_std=0.01, seed=m + r))
     ld = wl.padded_ld(prob.P, 4)
     x0 = wl.mc_init(W, prob, 0.7, ld=ld, seed=r)
     idx = None if B is None else wl.mc_batches(W, B, prob.n_obs, 1, seed=m)[0]
     c = 0.5 if B is None else 0.5 * prob.n_obs / B
     idx_d = None if idx is None else dev(idx)
-    batch = mc_batch(prob, idx_d, c)
+    batch = mc_batch(prob, idx_d, c, packed)
     pr = Pair(x0, np.array([0, W], dtype=np.int32), P=prob.P, largest_batch=batch)
     pr.g.fill_(123.0)                       # stale contents must be overwritten, padding zeroed
     pr.ora.grad_loss_mc(m, n, r, prob.rows, prob.cols, prob.vals, idx, c)
@@ -99,7 +109,7 @@ def test_lsgd_steps_minibatch_groups_stale_leaders():
         rl, rg = wl.refresh_masks(t, 4, G)
         pr.ora.grad_loss_mc(prob.m, prob.n, prob.r, prob.rows, prob.cols, prob.vals, idx[t], c)
         pr.ora.select(rl, rg); pr.ora.update(0.005, 0.1, 0.05, rl, rg)
-        pr.pop.step(mc_batch(prob, idx_d[t], c), 0.005, 0.1, 0.05, rl, rg)
+        pr.pop.step(mc_batch(prob, idx_d[t], c, packed=(t % 2 == 1)), 0.005, 0.1, 0.05, rl, rg)
         if not pr.check_leaders(rl, rg):
             pr.resync_from_oracle()
         if t == 0:
