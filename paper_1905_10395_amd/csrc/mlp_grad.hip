@@ -50,11 +50,28 @@ constexpr int kGemmThreads = 256;
 constexpr int kBK = 64;          // contraction tile
 constexpr int kLdk = kBK + 8;    // padded LDS row (bf16 elements): 144 B
 
-// 16-byte chunk position inside an LDS row; rows of a transposed-staged tile
-// are swizzled so that the transposing 8-byte writes spread over all banks.
+// 16-byte chunk position inside an LDS row.  Rows of a transposed-staged tile
+// are rotated by (row / 16): constant over the 16 consecutive rows that one
+// pass of a 16-byte fragment read touches (those stay conflict-free thanks to
+// the odd row stride), and different for the eight row groups whose 8-byte
+// transposing writes share a pass, which spreads them over all banks.
 template <bool SWZ> __device__ __forceinline__ int lds_chunk(int row, int chunk)
 {
-    return SWZ ? (chunk ^ ((row >> 3) & 7)) : chunk;
+    return SWZ ? ((chunk + (row >> 4)) & 7) : chunk;
+}
+
+// Thread -> (n-group, k-group) of the transposing stage.  With four k-rows per
+// thread the sixteen lanes of a write pass hold both k-halves of a 16-byte
+// chunk and eight n-groups that are two apart.
+template <int BN> __device__ __forceinline__ void trans_map(int tid, int& ng, int& kg)
+{
+    if (BN == 128) {
+        kg = (tid & 1) | ((tid >> 5) << 1);
+        ng = (((tid >> 1) & 7) << 1) | ((tid >> 4) & 1);
+    } else {
+        ng = tid % (BN / 8);
+        kg = tid / (BN / 8);
+    }
 }
 
 template <int BM, int BN, bool TRANS_B, int EPI>
@@ -96,7 +113,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
             ra[c] = *reinterpret_cast<const u32x4*>(A + (int64_t)row * g.lda + k0 + ch * 8);
         }
         if (TRANS_B) {
-            const int ng = tid % (BN / 8), kg = tid / (BN / 8);
+            int ng, kg;
+            trans_map<BN>(tid, ng, kg);
 #pragma unroll
             for (int q = 0; q < KK; ++q)
                 rb[q] = *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + kg * KK + q) * g.ldb + n0 + ng * 8);
@@ -117,7 +135,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
             *reinterpret_cast<u32x4*>(as + row * kLdk + ch * 8) = ra[c];
         }
         if (TRANS_B) {
-            const int ng = tid % (BN / 8), kg = tid / (BN / 8);
+            int ng, kg;
+            trans_map<BN>(tid, ng, kg);
             const int kk0 = kg * KK;               // first k of this thread's micro-tile
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
