@@ -75,7 +75,7 @@ template <int BN> __device__ __forceinline__ void trans_map(int tid, int& ng, in
 }
 
 template <int BM, int BN, bool TRANS_B, int EPI>
-__global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
 {
     constexpr int WTM = BM / 2, WTN = BN / 2;        // 2 x 2 wavefronts
     constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wavefront
@@ -102,10 +102,12 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    u32x4 ra[A_CHUNKS];
-    u32x4 rb[TRANS_B ? KK : B_CHUNKS];
+    // two register stages: the loads of k-steps kt+1 and kt+2 are in flight while kt is multiplied
+    constexpr int RB = TRANS_B ? KK : B_CHUNKS;
+    u32x4 ra0[A_CHUNKS], ra1[A_CHUNKS];
+    u32x4 rb0[RB], rb1[RB];
 
-    auto load_global = [&](int kt) {
+    auto load_global = [&](int kt, u32x4* ra, u32x4* rb) {
         const int k0 = kt * kBK;
 #pragma unroll
         for (int c = 0; c < A_CHUNKS; ++c) {
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
             }
         }
     };
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int buf, const u32x4* ra, const u32x4* rb) {
         uint16_t* as = As + buf * BM * kLdk;
         uint16_t* bs = Bs + buf * BN * kLdk;
 #pragma unroll
@@ -162,36 +164,49 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(GemmArgs g)
         }
     };
 
-    const int nk = g.K / kBK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) load_global(kt + 1);
+    // All fragments of a k-step are read from LDS first (one exposed LDS latency per k-step, hidden by
+    // the other wavefront of the SIMD), then the MFMAs issue back to back.
+    auto compute = [&](int buf) {
         const uint16_t* as = As + buf * BM * kLdk;
         const uint16_t* bs = Bs + buf * BN * kLdk;
+        bf16x8 af[kBK / 16][TM], bfr[kBK / 16][TN];
 #pragma unroll
         for (int kk = 0; kk < kBK / 16; ++kk) {
-            bf16x8 af[TM], bfr[TN];
             const int ch = kk * 2 + (lane >> 5);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = wm * WTM + i * 32 + (lane & 31);
-                af[i] = *reinterpret_cast<const bf16x8*>(as + row * kLdk + ch * 8);
+                af[kk][i] = *reinterpret_cast<const bf16x8*>(as + row * kLdk + ch * 8);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = wn * WTN + j * 32 + (lane & 31);
-                bfr[j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + lds_chunk<TRANS_B>(row, ch) * 8);
+                bfr[kk][j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + lds_chunk<TRANS_B>(row, ch) * 8);
             }
+        }
+#pragma unroll
+        for (int kk = 0; kk < kBK / 16; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) store_lds(buf ^ 1);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
+    };
+
+    const int nk = g.K / kBK;
+    load_global(0, ra0, rb0);
+    if (nk > 1) load_global(1, ra1, rb1);
+    store_lds(0, ra0, rb0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 2) {
+        if (kt + 2 < nk) load_global(kt + 2, ra0, rb0);
+        compute(0);
+        if (kt + 1 < nk) store_lds(1, ra1, rb1);
+        __syncthreads();
+        if (kt + 1 >= nk) break;
+        if (kt + 3 < nk) load_global(kt + 3, ra1, rb1);
+        compute(1);
+        if (kt + 2 < nk) store_lds(0, ra0, rb0);
         __syncthreads();
     }
 
