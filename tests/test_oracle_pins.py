@@ -466,3 +466,4 @@ def test_mlp_first_layer_is_a_softmax_regression_closed_form():
     dq = torch.tensor(d, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
     np.testing.assert_allclose(g[0, :28].reshape(4, 7), dq.T @ Xd, rtol=1e-6, atol=1e-7)
     np.testing.assert_allclose(g[0, 28:32], dq.sum(0), rtol=1e-6, atol=1e-7)
+
