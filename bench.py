@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of the batched LSGD step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c4]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5]
 
 Prints ONE JSON line.  `value` is worker-steps/s (W workers x steps / seconds)
 of the whole step with every input already resident in HBM.  `roofline`
@@ -26,6 +26,24 @@ import numpy as np
 import torch
 
 import workloads as wl
+
+# HBM bytes of one pull update on the 32 x 11,689,512 stress, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by
+# reference kernels of known size (profiles/pull_update_stress_32x11689512_hbm_traffic.md).  Valid only for the
+# kernel source they were taken on: reported as null once csrc/pull_update.hip differs.
+PULL_TRAFFIC = {"source_sha256_16": "58e2a72b3a09675e", "bytes_per_launch": 7.668e9, "W": 32, "P": 11_689_512}
+
+
+def _pull_traffic(W, P):
+    import hashlib
+    src = os.path.join(ROOT, "paper_1905_10395_amd", "csrc", "pull_update.hip")
+    try:
+        cur = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    if cur != PULL_TRAFFIC["source_sha256_16"] or (W, P) != (PULL_TRAFFIC["W"], PULL_TRAFFIC["P"]):
+        return None
+    return PULL_TRAFFIC["bytes_per_launch"]
+
 
 METRIC = "worker-steps/sec and pull-update HBM GB/s (% of peak) at W workers, 1 MI355X"
 HBM_PEAK_GBS = 8000.0
@@ -59,7 +77,7 @@ def _timed_steps(step_fn, steps, warmup):
 # ------------------------------------------------------------------------------------------
 # C4: pull-update bandwidth stress (leader selection + fused pull/momentum update only)
 # ------------------------------------------------------------------------------------------
-def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512):
+def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512, copy_ref=False):
     ld = wl.padded_ld(P)
     gen = torch.Generator(device=DEV); gen.manual_seed(wl.MASTER_SEED)
     x = torch.randn((W, ld), device=DEV, generator=gen) * 0.05
@@ -69,6 +87,12 @@ def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512):
     batches = [L.ExternalBatch(losses[i]) for i in range(16)]
     pop = L.Population(x, g, G, m=m, P=P, momentum=0.9)
     eta, lamL, lamG = 0.01, 0.1, 0.05
+    if copy_ref:
+        # a plain copy of known size (reads and writes W*ld*4 bytes each), the reference that scales
+        # the FETCH_SIZE / WRITE_SIZE counters of a profiled run
+        for _ in range(3):
+            m.copy_(g)
+        m.zero_()
 
     def step(t):
         pop.step(batches[t % 16], eta, lamL, lamG)
@@ -89,7 +113,7 @@ def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512):
         "workload": f"pull-update stress: W={W} x P={P} fp32 in {G} groups, momentum 0.9, select+pull only",
         "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
         "roofline": {"kernel": "pull_rows_kernel<4,true> + pull_leaders_kernel<4,true>", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": _pull_traffic(W, P),
                      "bytes_per_launch": bytes_per_launch, "ms_per_launch": ms_pull},
         "ms_select": ms_sel,
     }
@@ -166,7 +190,7 @@ def run_c2(L, steps, warmup, data):
         "workload": f"matrix completion LSGD: 20000x20000 rank 32, 1% observed ({prob.n_obs}), W={W} in {G} groups, "
                     f"B={B}/worker/step, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps",
         "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
-        "roofline": {"kernel": "lsgd_grad_loss (matrix completion)", "bound": "hbm", "achieved": ach,
+        "roofline": {"kernel": "lsgd_grad_loss stage: mc_residual + mc_scan + mc_scatter + mc_reduce + mc_loss_finish kernels", "bound": "hbm", "achieved": ach,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": grad_bytes, "ms_per_launch": ms_grad},
         "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
@@ -299,6 +323,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stress", action="store_true", help="skip the extra pull-update stress measurement")
+    ap.add_argument("--copy-ref", action="store_true", help="also run a plain device copy of one [W,ld] buffer (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; every population lives on a single device "
@@ -312,7 +337,7 @@ def main():
 
     stress = None
     if args.workload == "c4" or not args.no_stress:
-        stress = run_stress(L, min(args.steps, 100), min(args.warmup, 10))
+        stress = run_stress(L, min(args.steps, 100), min(args.warmup, 10), copy_ref=args.copy_ref)
     line = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
     if args.workload == "c4":
