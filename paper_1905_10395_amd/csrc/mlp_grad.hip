@@ -46,7 +46,6 @@ struct GemmArgs {
     float* C; int64_t sC; int64_t ldc;            // EPI_DW: fp32 [M][N]
 };
 
-constexpr int kGemmThreads = 256;
 constexpr int kBK = 64;          // contraction tile
 constexpr int kLdk = kBK + 8;    // padded LDS row (bf16 elements): 144 B
 
@@ -63,32 +62,40 @@ template <bool SWZ> __device__ __forceinline__ int lds_chunk(int row, int chunk)
 // Thread -> (n-group, k-group) of the transposing stage.  With four k-rows per
 // thread the sixteen lanes of a write pass hold both k-halves of a 16-byte
 // chunk and eight n-groups that are two apart.
-template <int BN> __device__ __forceinline__ void trans_map(int tid, int& ng, int& kg)
+template <int BN, int THREADS> __device__ __forceinline__ void trans_map(int tid, int& ng, int& kg)
 {
-    if (BN == 128) {
+    if (BN == 128 && THREADS == 256) {
         kg = (tid & 1) | ((tid >> 5) << 1);
         ng = (((tid >> 1) & 7) << 1) | ((tid >> 4) & 1);
+    } else if (BN == 256 && THREADS == 512) {
+        kg = (tid & 1) | ((tid >> 6) << 1);
+        ng = (((tid >> 1) & 7) << 1) | ((tid >> 4) & 1) | (((tid >> 5) & 1) << 4);
     } else {
         ng = tid % (BN / 8);
         kg = tid / (BN / 8);
     }
 }
 
-template <int BM, int BN, bool TRANS_B, int EPI>
-__global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
+// BM x BN output tile per workgroup, WVM x WVN wavefronts, each owning (BM/WVM) x (BN/WVN).
+// 128x128 / 128x64 with 2x2 wavefronts run two workgroups per CU; 256x256 with 2x4 wavefronts
+// (128x64 per wavefront, all 147 KB of LDS) moves half the bytes through LDS per flop.
+template <int BM, int BN, int WVM, int WVN, bool TRANS_B, int EPI>
+__global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_bf16_kernel(GemmArgs g)
 {
-    constexpr int WTM = BM / 2, WTN = BN / 2;        // 2 x 2 wavefronts
+    constexpr int kGemmThreads = 64 * WVM * WVN;
+    constexpr int WTM = BM / WVM, WTN = BN / WVN;
     constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wavefront
     constexpr int A_CHUNKS = BM * (kBK / 8) / kGemmThreads; // 16-byte chunks per thread
     constexpr int B_CHUNKS = BN * (kBK / 8) / kGemmThreads;
-    constexpr int KK = BN / 32;                      // k-rows per thread in the transposing stage
+    constexpr int KK = kBK * BN / 8 / kGemmThreads;  // k-rows per thread in the transposing stage
+    constexpr int STAGES = (WVM * WVN > 4) ? 1 : 2;  // register stages of global prefetch
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t* As = smem;                              // [2][BM][kLdk]
     uint16_t* Bs = smem + 2 * BM * kLdk;              // [2][BN][kLdk]
 
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
-    const int wm = wid >> 1, wn = wid & 1;
+    const int wm = wid / WVN, wn = wid % WVN;
     const int w = blockIdx.z;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
     const uint16_t* A = g.A + (int64_t)w * g.sA + (int64_t)m0 * g.lda;
@@ -104,8 +111,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
 
     // two register stages: the loads of k-steps kt+1 and kt+2 are in flight while kt is multiplied
     constexpr int RB = TRANS_B ? KK : B_CHUNKS;
-    u32x4 ra0[A_CHUNKS], ra1[A_CHUNKS];
-    u32x4 rb0[RB], rb1[RB];
+    u32x4 ra0[A_CHUNKS], ra1[STAGES == 2 ? A_CHUNKS : 1];
+    u32x4 rb0[RB], rb1[STAGES == 2 ? RB : 1];
 
     auto load_global = [&](int kt, u32x4* ra, u32x4* rb) {
         const int k0 = kt * kBK;
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
         }
         if (TRANS_B) {
             int ng, kg;
-            trans_map<BN>(tid, ng, kg);
+            trans_map<BN, kGemmThreads>(tid, ng, kg);
 #pragma unroll
             for (int q = 0; q < KK; ++q)
                 rb[q] = *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + kg * KK + q) * g.ldb + n0 + ng * 8);
@@ -138,7 +145,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
         }
         if (TRANS_B) {
             int ng, kg;
-            trans_map<BN>(tid, ng, kg);
+            trans_map<BN, kGemmThreads>(tid, ng, kg);
             const int kk0 = kg * KK;               // first k of this thread's micro-tile
 #pragma unroll
             for (int n = 0; n < 8; ++n) {
@@ -164,50 +171,65 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
         }
     };
 
-    // All fragments of a k-step are read from LDS first (one exposed LDS latency per k-step, hidden by
-    // the other wavefront of the SIMD), then the MFMAs issue back to back.
     auto compute = [&](int buf) {
         const uint16_t* as = As + buf * BM * kLdk;
         const uint16_t* bs = Bs + buf * BN * kLdk;
-        bf16x8 af[kBK / 16][TM], bfr[kBK / 16][TN];
 #pragma unroll
         for (int kk = 0; kk < kBK / 16; ++kk) {
+            bf16x8 af[TM], bfr[TN];
             const int ch = kk * 2 + (lane >> 5);
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row = wm * WTM + i * 32 + (lane & 31);
-                af[kk][i] = *reinterpret_cast<const bf16x8*>(as + row * kLdk + ch * 8);
+                af[i] = *reinterpret_cast<const bf16x8*>(as + row * kLdk + ch * 8);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int row = wn * WTN + j * 32 + (lane & 31);
-                bfr[kk][j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + lds_chunk<TRANS_B>(row, ch) * 8);
+                bfr[j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + lds_chunk<TRANS_B>(row, ch) * 8);
             }
-        }
-#pragma unroll
-        for (int kk = 0; kk < kBK / 16; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
     };
 
+    // Pipeline.  LDS holds k-steps kt (being multiplied) and kt+1.  Each iteration first hands the
+    // register stage that has arrived to LDS (into the buffer nobody reads now) and re-issues it for
+    // a later k-step, then multiplies: LDS writes and global loads drain underneath the MFMAs.
+    // Two register stages (k-steps kt+1 and kt+2 in flight) where registers allow, else one.
     const int nk = g.K / kBK;
-    load_global(0, ra0, rb0);
-    if (nk > 1) load_global(1, ra1, rb1);
-    store_lds(0, ra0, rb0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; kt += 2) {
-        if (kt + 2 < nk) load_global(kt + 2, ra0, rb0);
-        compute(0);
-        if (kt + 1 < nk) store_lds(1, ra1, rb1);
+    if (STAGES == 2) {
+        load_global(0, ra0, rb0);
+        if (nk > 1) load_global(1, ra1, rb1);
+        store_lds(0, ra0, rb0);
+        if (nk > 2) load_global(2, ra0, rb0);
         __syncthreads();
-        if (kt + 1 >= nk) break;
-        if (kt + 3 < nk) load_global(kt + 3, ra1, rb1);
-        compute(1);
-        if (kt + 2 < nk) store_lds(0, ra0, rb0);
+        for (int kt = 0; kt < nk; kt += 2) {
+            if (kt + 1 < nk) store_lds(1, ra1, rb1);
+            if (kt + 3 < nk) load_global(kt + 3, ra1, rb1);
+            compute(0);
+            __syncthreads();
+            if (kt + 1 >= nk) break;
+            if (kt + 2 < nk) store_lds(0, ra0, rb0);
+            if (kt + 4 < nk) load_global(kt + 4, ra0, rb0);
+            compute(1);
+            __syncthreads();
+        }
+    } else {
+        load_global(0, ra0, rb0);
+        store_lds(0, ra0, rb0);
+        if (nk > 1) load_global(1, ra0, rb0);
         __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int buf = kt & 1;
+            if (kt + 1 < nk) store_lds(buf ^ 1, ra0, rb0);
+            if (kt + 2 < nk) load_global(kt + 2, ra0, rb0);
+            compute(buf);
+            __syncthreads();
+        }
     }
 
     // epilogue: lane holds column n = lane%32 and rows (lane/32)*4 + 8*(v/4) + v%4 of each 32x32 tile
@@ -249,43 +271,43 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_bf16_kernel(GemmArgs g)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = mb + 8 * (v >> 2) + (v & 3);
-                    __builtin_nontemporal_store(acc[i][j][v], C + (int64_t)m * g.ldc + n);
+                    C[(int64_t)m * g.ldc + n] = acc[i][j][v];
                 }
             }
         }
 }
 
-template <int BM, int BN, bool TRANS_B, int EPI>
+template <int BM, int BN, int WVM, int WVN, bool TRANS_B, int EPI>
 static void launch_gemm(const GemmArgs& g, int W, hipStream_t s)
 {
     const size_t lds = (size_t)2 * (BM + BN) * kLdk * sizeof(uint16_t);
     static bool configured = false;
     if (!configured) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, TRANS_B, EPI>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, WVM, WVN, TRANS_B, EPI>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         configured = true;
     }
     dim3 grid((unsigned)(g.N / BN), (unsigned)(g.M / BM), (unsigned)W);
-    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, TRANS_B, EPI>), grid, dim3(kGemmThreads), lds, s, g);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WVM, WVN, TRANS_B, EPI>), grid, dim3(64 * WVM * WVN), lds, s, g);
 }
 
-static bool aligned_for_mfma(const GemmArgs& g, bool trans_b)
+static bool aligned_for_mfma(const GemmArgs& g)
 {
     auto a16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
-    bool ok = a16(g.A) && a16(g.B) && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.sA % 8 == 0 && g.sB % 8 == 0;
-    (void)trans_b;
-    return ok;
+    return a16(g.A) && a16(g.B) && g.lda % 8 == 0 && g.ldb % 8 == 0 && g.sA % 8 == 0 && g.sB % 8 == 0;
 }
 
-// Picks a tile so that the grid fills the chip; returns false when no MFMA tile fits the shape.
+// Picks the largest tile whose grid still fills the chip; returns false when no MFMA tile fits the shape.
 template <bool TRANS_B, int EPI>
 static bool try_mfma(const GemmArgs& g, int W, hipStream_t s)
 {
-    if (g.K % kBK || g.M % 128 || g.N % 64 || !aligned_for_mfma(g, TRANS_B)) return false;
+    if (g.K % kBK || g.M % 128 || g.N % 64 || !aligned_for_mfma(g)) return false;
     if (EPI == EPI_DX && (g.ldoutT % 4 || (reinterpret_cast<uintptr_t>(g.outT) & 7u) || g.sOutT % 4)) return false;
+    const int64_t blocks256 = (g.M % 256 == 0 && g.N % 256 == 0) ? (int64_t)(g.M / 256) * (g.N / 256) * W : 0;
     const int64_t blocks128 = (int64_t)(g.M / 128) * (g.N / 128) * W;
-    if (g.N % 128 == 0 && blocks128 >= 256) launch_gemm<128, 128, TRANS_B, EPI>(g, W, s);
-    else launch_gemm<128, 64, TRANS_B, EPI>(g, W, s);
+    if (blocks256 >= 256) launch_gemm<256, 256, 2, 4, TRANS_B, EPI>(g, W, s);
+    else if (g.N % 128 == 0 && blocks128 >= 256) launch_gemm<128, 128, 2, 2, TRANS_B, EPI>(g, W, s);
+    else launch_gemm<128, 64, 2, 2, TRANS_B, EPI>(g, W, s);
     return true;
 }
 
@@ -483,37 +505,61 @@ __global__ __launch_bounds__(256) void dw_narrow_kernel(const uint16_t* __restri
 }
 
 // dprev[b][i..i+7] = bf16(sum_o delta[b][o] Wq[o][i..i+7]) .* [h > 0] for a narrow delta (few classes).
-__global__ __launch_bounds__(128) void dx_narrow_kernel(const uint16_t* __restrict__ delta, int64_t sD, const uint16_t* __restrict__ Wq, int64_t sW,
+// A workgroup owns 64 samples x 64 columns: thread (b, 8-column chunk).  The row-major result is
+// stored directly (128 contiguous bytes per sample); the transposed copy goes through an LDS tile so
+// that it too leaves as 128-byte runs (64 samples of one column).
+__global__ __launch_bounds__(512) void dx_narrow_kernel(const uint16_t* __restrict__ delta, int64_t sD, const uint16_t* __restrict__ Wq, int64_t sW,
                                                         const uint16_t* __restrict__ H, int64_t sH, int64_t ldh, int B, int din, int dout,
                                                         uint16_t* __restrict__ dprev, uint16_t* __restrict__ dprevT, int64_t sP)
 {
-    const int w = blockIdx.z, b = blockIdx.y;
-    const int c = blockIdx.x * 128 + threadIdx.x;
-    if (c >= din / 8) return;
-    const uint16_t* d = delta + (int64_t)w * sD + (int64_t)b * dout;
-    const uint16_t* Wm = Wq + (int64_t)w * sW + (int64_t)c * 8;
-    float acc[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) acc[t] = 0.f;
-    for (int o = 0; o < dout; ++o) {
-        const float dv = bf16_to_f32(d[o]);
-        float a[8];
-        unpack8(*reinterpret_cast<const u32x4*>(Wm + (int64_t)o * din), a);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) acc[t] = fmaf(dv, a[t], acc[t]);
-    }
-    const u32x4 hm = *reinterpret_cast<const u32x4*>(H + (int64_t)w * sH + (int64_t)b * ldh + (int64_t)c * 8);
+    constexpr int kLd = 72;                                   // padded tile row (bf16), 144 B
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * kLd];   // [column][sample]
+    const int w = blockIdx.z;
+    const int t = threadIdx.x, cl = t & 7, bl = t >> 3;
+    const int b = blockIdx.y * 64 + bl;
+    const int c = blockIdx.x * 8 + cl;                        // 16-byte chunk = 8 columns
+    const bool live = b < B && c < din / 8;
     uint32_t pk[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        const uint32_t hb = (t & 1) ? (hm[t >> 1] >> 16) : (hm[t >> 1] & 0xFFFFu);
-        pk[t] = hb ? (uint32_t)f32_to_bf16_rne(acc[t]) : 0u;
-    }
-    u32x4 o4 = {pk[0] | (pk[1] << 16), pk[2] | (pk[3] << 16), pk[4] | (pk[5] << 16), pk[6] | (pk[7] << 16)};
-    *reinterpret_cast<u32x4*>(dprev + (int64_t)w * sP + (int64_t)b * din + (int64_t)c * 8) = o4;
-    uint16_t* dT = dprevT + (int64_t)w * sP + (int64_t)c * 8 * B + b;
+    for (int q = 0; q < 8; ++q) pk[q] = 0;
+    if (live) {
+        const uint16_t* d = delta + (int64_t)w * sD + (int64_t)b * dout;
+        const uint16_t* Wm = Wq + (int64_t)w * sW + (int64_t)c * 8;
+        float acc[8];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) dT[(int64_t)t * B] = (uint16_t)pk[t];
+        for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+        for (int o = 0; o < dout; ++o) {
+            const float dv = bf16_to_f32(d[o]);
+            float a[8];
+            unpack8(*reinterpret_cast<const u32x4*>(Wm + (int64_t)o * din), a);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[q] = fmaf(dv, a[q], acc[q]);
+        }
+        const u32x4 hm = *reinterpret_cast<const u32x4*>(H + (int64_t)w * sH + (int64_t)b * ldh + (int64_t)c * 8);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t hb = (q & 1) ? (hm[q >> 1] >> 16) : (hm[q >> 1] & 0xFFFFu);
+            pk[q] = hb ? (uint32_t)f32_to_bf16_rne(acc[q]) : 0u;
+        }
+        u32x4 o4 = {pk[0] | (pk[1] << 16), pk[2] | (pk[3] << 16), pk[4] | (pk[5] << 16), pk[6] | (pk[7] << 16)};
+        *reinterpret_cast<u32x4*>(dprev + (int64_t)w * sP + (int64_t)b * din + (int64_t)c * 8) = o4;
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) tile[(cl * 8 + q) * kLd + bl] = (uint16_t)pk[q];
+    __syncthreads();
+    // thread (column il, 8-sample chunk): 16 bytes of the transposed copy
+    const int il = t >> 3, bc = t & 7;
+    const int col = blockIdx.x * 64 + il;
+    const int b0 = blockIdx.y * 64 + bc * 8;
+    if (col < din && b0 < B) {
+        uint16_t* dst = dprevT + (int64_t)w * sP + (int64_t)col * B + b0;
+        const uint16_t* src = tile + il * kLd + bc * 8;
+        if (b0 + 8 <= B && (B & 7) == 0) {
+            *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src);
+        } else {
+            for (int q = 0; q < 8 && b0 + q < B; ++q) dst[q] = src[q];
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void zero_pad_kernel(float* __restrict__ g, int64_t P, int64_t ld)
@@ -663,8 +709,8 @@ hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, fl
             const bool vec8 = din % 8 == 0 && ld % 8 == 0 && woff[k] % 8 == 0 && a16(xb) && a16(Hin) && sHin % 8 == 0;
             if (try_mfma<true, EPI_DX>(a, W, s)) {
             } else if (vec8 && dout <= 64) {
-                dim3 grid((unsigned)((din / 8 + 127) / 128), (unsigned)B, (unsigned)W);
-                hipLaunchKernelGGL(dx_narrow_kernel, grid, dim3(128), 0, s, sc16 + p.d[k], sW16, xb + woff[k], ld, Hin, sHin,
+                dim3 grid((unsigned)((din / 8 + 7) / 8), (unsigned)((B + 63) / 64), (unsigned)W);
+                hipLaunchKernelGGL(dx_narrow_kernel, grid, dim3(512), 0, s, sc16 + p.d[k], sW16, xb + woff[k], ld, Hin, sHin,
                                    (int64_t)din, B, din, dout, sc16 + p.d[k - 1], sc16 + p.dT[k - 1], sW16);
             } else {
                 dim3 grid((unsigned)((din + 255) / 256), (unsigned)B, (unsigned)W);

@@ -70,6 +70,9 @@ SHAPES = [
     ([512, 1024, 10], 8, 128),                # d-weight on 128x128 tiles
     ([64, 512, 256, 10], 64, 128),            # forward and d-input on 128x128 tiles
     ([128, 128, 10], 2, 256),                 # two M tiles, K = 256 for d-weight
+    ([512, 1024, 10], 32, 128),               # d-weight on 256x256 tiles (8 wavefronts)
+    ([64, 1024, 10], 64, 256),                # forward on 256x256 tiles
+    ([64, 1024, 256, 10], 64, 256),           # forward and d-input on 256x256 tiles
 ]
 
 
