@@ -91,6 +91,26 @@ def pull_update(x, m, g, Z, P, off, lead, glead, eta, lam_L, lam_G, mu=0.0,
                                   C.c_float(weight_decay))
 
 
+def leader_pull(x, Z, P, off, lead, glead, lam_L, lam_G, refresh_local=None, refresh_global=1):
+    """Algorithm 1's communication pull, in place on x and Z[(G+1), ld]."""
+    W, ld = x.shape
+    G = int(off.shape[0]) - 1
+    lib().lsgd_oracle_leader_pull(_f32(x), _f32(Z), C.c_int(W), C.c_int64(int(P)), C.c_int64(int(ld)), C.c_int(G), _i32(off),
+                                  _i32(lead), C.c_int32(int(glead[0])), _u8(refresh_local), C.c_int(int(refresh_global)),
+                                  C.c_float(lam_L), C.c_float(lam_G))
+
+
+def smooth_losses(window, t, losses, out):
+    """window: float32 [K, W] ring (in place); out: float32 [W]."""
+    K, W = window.shape
+    lib().lsgd_oracle_smooth_losses(_f32(window), C.c_int(K), C.c_int64(int(t)), _f32(losses), C.c_int(W), _f32(out))
+
+
+def center(x, P, out):
+    W, ld = x.shape
+    lib().lsgd_oracle_center(_f32(x), C.c_int(W), C.c_int64(int(P)), C.c_int64(int(ld)), _f32(out))
+
+
 def mc_grad_loss(x, m, n, r, rows, cols, vals, batch_idx, c, g, losses):
     """batch_idx: int32 [W,B] or None (every observed entry, for every worker)."""
     W, ld = x.shape
@@ -145,6 +165,9 @@ class Population:
 
     def select(self, refresh_local=None, refresh_global=1):
         self.gaps = select_leaders(self.losses, self.off, self.lead, self.glead, refresh_local, refresh_global)
+
+    def leader_pull(self, lam_L, lam_G, refresh_local=None, refresh_global=1):
+        leader_pull(self.x, self.Z, self.P, self.off, self.lead, self.glead, lam_L, lam_G, refresh_local, refresh_global)
 
     def update(self, eta, lam_L, lam_G, refresh_local=None, refresh_global=1):
         pull_update(self.x, self.m, self.g, self.Z, self.P, self.off, self.lead, self.glead,

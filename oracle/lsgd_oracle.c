@@ -22,7 +22,8 @@
  * quadratic and the bound of Theorem 2; monotone leader value (Lemma
  * "leader_descent"); the sinc example's optimum -0.2172 (supplement Table 1);
  * grad F = (XX^T - M)X for the dense PSD problem; finite differences;
- * brute-force argmin.
+ * brute-force argmin; Algorithm 1's communication pull as two successive
+ * single-leader interpolations; window mean and column mean against numpy.
  *
  * Parity unpinned by the paper (fixed by declaration): where momentum enters
  * (heavy ball on the full direction by default), the bf16 rounding points of
@@ -140,6 +141,66 @@ void lsgd_oracle_pull_update(float* x, float* m, const float* g, float* Z,
             }
             xi[p] = (float)(xv - eta * step);
         }
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Communication step of Algorithm 1: after re-selecting leaders, every worker
+ * of a re-selected group is pulled to its local leader, x <- x - lam (x - x~^j),
+ * and at a global communication to the global leader, x <- x - lam_G (x - x~).
+ * No gradient, no learning rate, momentum untouched.  Both pulls use the
+ * leaders' parameters as they were when selected (copied to Z first); a
+ * leader's pull to itself is zero.                                      */
+/* ------------------------------------------------------------------ */
+void lsgd_oracle_leader_pull(float* x, float* Z, int W, int64_t P, int64_t ld, int G, const int32_t* off,
+                             const int32_t* lead, int32_t glead, const uint8_t* refresh_local, int refresh_global,
+                             float lamL_f, float lamG_f)
+{
+    for (int j = 0; j < G; ++j)
+        if (!refresh_local || refresh_local[j])
+            memcpy(Z + (int64_t)j * ld, x + (int64_t)lead[j] * ld, sizeof(float) * (size_t)P);
+    if (refresh_global)
+        memcpy(Z + (int64_t)G * ld, x + (int64_t)glead * ld, sizeof(float) * (size_t)P);
+    #pragma omp parallel for schedule(static)
+    for (int i = 0; i < W; ++i) {
+        int j = 0;
+        while (!(off[j] <= i && i < off[j + 1])) ++j;
+        const double cL = (!refresh_local || refresh_local[j]) ? (double)lamL_f : 0.0;
+        const double cG = refresh_global ? (double)lamG_f : 0.0;
+        const float* zL = Z + (int64_t)j * ld;
+        const float* zG = Z + (int64_t)G * ld;
+        float* xi = x + (int64_t)i * ld;
+        for (int64_t p = 0; p < P; ++p) {
+            double y = (double)xi[p];
+            if (cL != 0.0) y = y - cL * (y - (double)zL[p]);
+            if (cG != 0.0) y = y - cG * (y - (double)zG[p]);
+            xi[p] = (float)y;
+        }
+    }
+}
+
+/* Selection loss smoothed over the last K minibatches (Section 4.1: the leader is
+ * chosen from the average training loss over the last 10 / 64 batches).
+ * window[K][W] is a ring: slot t % K receives the new losses; out = mean of
+ * the min(t+1, K) newest slots.                                          */
+void lsgd_oracle_smooth_losses(float* window, int K, int64_t t, const float* losses, int W, float* out)
+{
+    memcpy(window + (t % K) * W, losses, sizeof(float) * (size_t)W);
+    const int64_t n = (t + 1 < K) ? t + 1 : K;
+    for (int i = 0; i < W; ++i) {
+        double s = 0.0;
+        for (int64_t q = 0; q < n; ++q) s += (double)window[q * W + i];
+        out[i] = (float)(s / (double)n);
+    }
+}
+
+/* Center variable reported at test time (Section 4.1): the average of all workers' parameters. */
+void lsgd_oracle_center(const float* x, int W, int64_t P, int64_t ld, float* out)
+{
+    for (int64_t p = 0; p < P; ++p) {
+        double s = 0.0;
+        for (int i = 0; i < W; ++i) s += (double)x[(int64_t)i * ld + p];
+        out[p] = (float)(s / (double)W);
     }
 }
 

@@ -467,3 +467,59 @@ def test_mlp_first_layer_is_a_softmax_regression_closed_form():
     np.testing.assert_allclose(g[0, :28].reshape(4, 7), dq.T @ Xd, rtol=1e-6, atol=1e-7)
     np.testing.assert_allclose(g[0, 28:32], dq.sum(0), rtol=1e-6, atol=1e-7)
 
+
+# ----------------------------------------------------------------------------
+# Algorithm 1's communication pull, smoothed selection loss, center variable
+# ----------------------------------------------------------------------------
+def test_leader_pull_is_two_successive_interpolations():
+    """Algorithm 1: x <- x - lam (x - x~^j), then x <- x - lam_G (x - x~); leaders' own pulls vanish."""
+    r = wl.stream("alg1_pin")
+    W, P = 6, 21
+    x0 = r.standard_normal((W, P)).astype(np.float32)
+    off = np.array([0, 3, 6], dtype=np.int32)
+    pop = oracle.Population(x0, off)
+    pop.losses[:] = np.array([3, 1, 2, 0.5, 4, 5], dtype=np.float32)
+    pop.select()
+    assert pop.lead.tolist() == [1, 3] and pop.glead[0] == 3
+    pop.leader_pull(0.25, 0.125)
+    lam, lg = float(np.float32(0.25)), float(np.float32(0.125))
+    xd = x0.astype(np.float64)
+    zl = xd[[1, 1, 1, 3, 3, 3]]
+    y = xd - lam * (xd - zl)                      # phase 1 leaves both local leaders where they are
+    np.testing.assert_array_equal(y[[1, 3]], xd[[1, 3]])
+    want = y - lg * (y - xd[3])                   # phase 2 pulls to the (unmoved) global leader
+    np.testing.assert_allclose(pop.x, want, rtol=1e-6, atol=1e-7)
+    np.testing.assert_array_equal(pop.x[3], x0[3])          # the global leader does not move at all
+    np.testing.assert_array_equal(pop.Z, x0[[1, 3, 3]])
+    # lam = 1 puts every follower exactly on its leader; lam_G = 1 puts everybody on the global leader
+    pop = oracle.Population(x0, off); pop.losses[:] = np.array([3, 1, 2, 0.5, 4, 5], dtype=np.float32); pop.select()
+    pop.leader_pull(1.0, 0.0)
+    np.testing.assert_array_equal(pop.x, x0[[1, 1, 1, 3, 3, 3]])
+    pop.select(); pop.leader_pull(0.0, 1.0)
+    np.testing.assert_array_equal(pop.x, np.tile(x0[3], (W, 1)))
+    # only refreshed groups are pulled locally; without a global refresh there is no global pull
+    pop = oracle.Population(x0, off); pop.losses[:] = np.array([3, 1, 2, 0.5, 4, 5], dtype=np.float32)
+    m = np.array([0, 1], dtype=np.uint8)
+    pop.select(m, 0); pop.leader_pull(0.5, 0.5, m, 0)
+    np.testing.assert_array_equal(pop.x[:3], x0[:3])
+    np.testing.assert_allclose(pop.x[3:], 0.5 * (xd[3:] + xd[3]), rtol=1e-6, atol=1e-7)
+
+
+def test_smoothed_loss_is_the_mean_of_the_last_k_batches():
+    r = wl.stream("smooth_pin")
+    W, K = 5, 4
+    window = np.zeros((K, W), dtype=np.float32)
+    hist = []
+    out = np.zeros(W, dtype=np.float32)
+    for t in range(11):
+        l = r.random(W, dtype=np.float32); hist.append(l)
+        oracle.smooth_losses(window, t, l, out)
+        np.testing.assert_allclose(out, np.mean(np.array(hist[-K:], dtype=np.float64), axis=0), rtol=1e-6)
+
+
+def test_center_variable_is_the_column_mean():
+    r = wl.stream("center_pin")
+    x = r.standard_normal((7, 40)).astype(np.float32)
+    out = np.zeros(33, dtype=np.float32)
+    oracle.center(x, 33, out)
+    np.testing.assert_allclose(out, x[:, :33].astype(np.float64).mean(0), rtol=1e-6, atol=1e-7)
