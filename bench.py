@@ -30,7 +30,7 @@ import workloads as wl
 # HBM bytes of one pull update on the 32 x 11,689,512 stress, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by
 # reference kernels of known size (profiles/pull_update_stress_32x11689512_hbm_traffic.md).  Valid only for the
 # kernel source they were taken on: reported as null once csrc/pull_update.hip differs.
-PULL_TRAFFIC = {"source_sha256_16": "58e2a72b3a09675e", "bytes_per_launch": 7.668e9, "W": 32, "P": 11_689_512}
+PULL_TRAFFIC = {"source_sha256_16": "8ead91ff44c23752", "bytes_per_launch": 7.668e9, "W": 32, "P": 11_689_512}
 
 
 def _pull_traffic(W, P):
@@ -112,7 +112,7 @@ def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512, copy_ref=False):
     out = {
         "workload": f"pull-update stress: W={W} x P={P} fp32 in {G} groups, momentum 0.9, select+pull only",
         "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
-        "roofline": {"kernel": "pull_rows_kernel<4,true> + pull_leaders_kernel<4,true>", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": "pull_rows_kernel<4,1> + pull_leaders_kernel<4,1>", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": _pull_traffic(W, P),
                      "bytes_per_launch": bytes_per_launch, "ms_per_launch": ms_pull},
         "ms_select": ms_sel,
@@ -186,6 +186,16 @@ def run_c2(L, steps, warmup, data):
     grad_bytes = W * (2 * 4.0 * prob.P + 16.0 * B)
     ach = grad_bytes / (ms_grad * 1e-3) / 1e9
     lossv = pop.get_losses()
+
+    # the same workload on Algorithm 1's schedule (small pulls to the kept copies every iteration,
+    # selection + communication pull every tau iterations), and the center variable
+    gamL, gamG = 0.1 / tau, 0.05 / tau
+
+    def step_alg1(t):
+        pop.step_alg1(batches[t % K], eta, gamL, gamG, lamL, lamG, (L.COMM_LOCAL | L.COMM_GLOBAL) if t % tau == 0 else 0)
+    secs_alg1 = _timed_steps(step_alg1, steps, warmup)
+    center = torch.empty(ld, device=DEV)
+    ms_center = _events_ms(lambda i: pop.center(center), reps)
     out = {
         "workload": f"matrix completion LSGD: 20000x20000 rank 32, 1% observed ({prob.n_obs}), W={W} in {G} groups, "
                     f"B={B}/worker/step, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps",
@@ -196,6 +206,9 @@ def run_c2(L, steps, warmup, data):
         "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
         "pull_update_GBs": W * 12.0 * prob.P / (ms_pull * 1e-3) / 1e9,
         "final_mean_loss": float(np.mean(lossv)),
+        "alg1_schedule": {"value": W * steps / secs_alg1, "unit": "worker-steps/s", "ms_per_step": secs_alg1 / steps * 1e3,
+                          "comm_every": tau},
+        "center": {"ms": ms_center, "GBs": 4.0 * (W + 1) * prob.P / (ms_center * 1e-3) / 1e9},
     }
     del pop
     return out
@@ -356,7 +369,7 @@ def main():
     line.update({"value": primary["value"], "unit": primary["unit"], "ms_per_step": primary["ms_per_step"],
                  "config": {"workload": primary["workload"]}, "roofline": primary["roofline"],
                  "cpu_baseline": cpu})
-    for k in ("stage_ms", "pull_update_GBs", "final_mean_loss", "ms_select"):
+    for k in ("stage_ms", "pull_update_GBs", "final_mean_loss", "ms_select", "alg1_schedule", "center"):
         if k in primary:
             line[k] = primary[k]
     if stress is not None:

@@ -183,6 +183,56 @@ lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, fl
 lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, float lambda_L,
                       float lambda_G, const uint8_t* refresh_local, int refresh_global);
 
+/* Communication pull of Algorithm 1 ("determine the local / global best
+ * workers", "pull to the local / global best workers"): captures every leader
+ * re-selected since the last update (copied from x before any row changes, and
+ * written to z_snapshot when it exists, also when its coefficient is 0), then
+ *   groups whose local leader was re-selected:  x <- x - lambda_L (x - z_local)
+ *   if the global leader was re-selected:        x <- x - lambda_G (x - z_global)
+ * in that order, element-wise, with no gradient, learning rate or momentum
+ * involved.  Groups (or the global term) with nothing re-selected are left
+ * alone.  LSGD_ERR_STATE if nothing was re-selected since the last update.     */
+lsgd_status lsgd_leader_pull(lsgd_population* pop, float lambda_L, float lambda_G);
+
+/* lsgd_step_alg1.comm bits */
+enum {
+    LSGD_COMM_LOCAL = 1,  /* local communication at this step  (n l tau   divides the iteration count) */
+    LSGD_COMM_GLOBAL = 2  /* global communication at this step (n l tau_G divides the iteration count) */
+};
+
+/* One iteration of Algorithm 1 for every worker at once:
+ *   grad_loss;  x <- x - eta g - gamma_L (x - z_local) - gamma_G (x - z_global)
+ *   with the kept leader copies (gamma_L = gamma/tau, gamma_G = gamma_G/tau_G,
+ *   not multiplied by eta; momentum, weight decay and flags of the population
+ *   apply to the gradient part as in lsgd_pull_update);
+ *   then, when comm has LSGD_COMM_LOCAL / LSGD_COMM_GLOBAL: select_leaders from
+ *   this iteration's losses (comm_local_mask: host [n_groups] choosing the
+ *   groups that communicate, NULL = all) followed by lsgd_leader_pull.
+ * Before the first iteration the caller initialises the leaders (Algorithm 1,
+ * "Initialize"): grad_loss, select_leaders(all), lsgd_leader_pull(0, 0).
+ * Needs z_snapshot.  eta must be non-zero when a gamma is.                      */
+lsgd_status lsgd_step_alg1(lsgd_population* pop, const lsgd_batch* batch, float eta, float gamma_L,
+                           float gamma_G, float lambda_L, float lambda_G, int comm,
+                           const uint8_t* comm_local_mask);
+
+/* Selection loss averaged over the last K minibatches (Section 4.1: leaders are
+ * determined from the average training loss over the last 10 or 64 batches).
+ *   window device [K, W] fp32 ring owned by the caller; slot t % K receives the
+ *          new losses (no initialisation needed: only filled slots are read)
+ *   t      0-based count of calls so far on this ring
+ *   losses device [W] new losses; NULL = the population's own buffer
+ *   out    device [W] mean over the min(t+1, K) newest slots, summed in slot
+ *          order in double; NULL = the population's own buffer (so that a
+ *          following lsgd_select_leaders(pop, NULL, ...) uses it); may alias losses. */
+lsgd_status lsgd_smooth_losses(lsgd_population* pop, float* window, int32_t K, int64_t t,
+                               const float* losses, float* out);
+
+/* Center variable (Section 4.1: the model reported at test time is the average
+ * of all workers' parameters): out[p] = (1/W) sum_i x[i, p], summed over i in
+ * order in double and rounded once.  out: device [P] (16-byte aligned for the
+ * fast path), must not overlap x.                                              */
+lsgd_status lsgd_center(lsgd_population* pop, float* out);
+
 /* Builds the 16-byte-record form of an observed-entry list (device to device, on
  * hip_stream): out[k] = {rows[k], cols[k], vals[k], 0}.  The list of observed
  * entries is fixed across steps (the paper's M and its observed set), so this is

@@ -15,6 +15,8 @@ LEADER_EXEMPT = 2
 PULL_UNSCALED_BY_ETA = 4
 MOMENTUM_GRAD_ONLY = 8
 WRITE_BF16_SHADOW = 16
+COMM_LOCAL = 1
+COMM_GLOBAL = 2
 
 BATCH_EXTERNAL, BATCH_MC, BATCH_MLP = 0, 1, 2
 
@@ -79,6 +81,11 @@ def lib():
         L.lsgd_pull_update.argtypes = [C.c_void_p, C.c_float, C.c_float, C.c_float]
         L.lsgd_step.argtypes = [C.c_void_p, C.POINTER(_Batch), C.c_float, C.c_float, C.c_float,
                                 C.POINTER(C.c_uint8), C.c_int]
+        L.lsgd_leader_pull.argtypes = [C.c_void_p, C.c_float, C.c_float]
+        L.lsgd_step_alg1.argtypes = [C.c_void_p, C.POINTER(_Batch), C.c_float, C.c_float, C.c_float, C.c_float, C.c_float,
+                                     C.c_int, C.POINTER(C.c_uint8)]
+        L.lsgd_smooth_losses.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
+        L.lsgd_center.argtypes = [C.c_void_p, C.c_void_p]
         L.lsgd_sync_shadow.argtypes = [C.c_void_p]
         L.lsgd_mc_pack_entries.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.lsgd_get_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -214,6 +221,22 @@ class Population:
     def step(self, batch, eta, lambda_L, lambda_G, refresh_local=None, refresh_global=1):
         _check(lib().lsgd_step(self._h, C.byref(batch.c), eta, lambda_L, lambda_G, self._mask(refresh_local),
                                int(refresh_global)))
+
+    def leader_pull(self, lambda_L, lambda_G):
+        _check(lib().lsgd_leader_pull(self._h, lambda_L, lambda_G))
+
+    def step_alg1(self, batch, eta, gamma_L, gamma_G, lambda_L, lambda_G, comm=0, comm_local_mask=None):
+        _check(lib().lsgd_step_alg1(self._h, C.byref(batch.c), eta, gamma_L, gamma_G, lambda_L, lambda_G, int(comm),
+                                    self._mask(comm_local_mask)))
+
+    def smooth_losses(self, window, t, losses=None, out=None):
+        """window: device float32 [K, W] ring."""
+        assert window.dtype == torch.float32 and window.is_contiguous() and window.shape[1] == self.W
+        _check(lib().lsgd_smooth_losses(self._h, _ptr(window), int(window.shape[0]), int(t), _ptr(losses), _ptr(out)))
+
+    def center(self, out):
+        assert out.dtype == torch.float32 and out.is_contiguous() and out.numel() >= self.P
+        _check(lib().lsgd_center(self._h, _ptr(out)))
 
     def sync_shadow(self):
         _check(lib().lsgd_sync_shadow(self._h))

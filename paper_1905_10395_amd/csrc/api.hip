@@ -344,7 +344,16 @@ lsgd_status do_select(lsgd_population* p, const float* losses, const uint8_t* re
     return LSGD_OK;
 }
 
-lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG)
+bool any_pending(const lsgd_population* p)
+{
+    bool any = p->pending_global;
+    for (int j = 0; j < p->cfg.n_groups; ++j) any = any || p->pending_local[(size_t)j];
+    return any;
+}
+
+// comm: Algorithm 1's communication pull (lamL, lamG are its lambdas; eta unused).
+// unscaled: the pulls of a gradient step are not multiplied by eta.
+lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG, bool unscaled, bool comm)
 {
     const int G = p->cfg.n_groups;
     PullParams q;
@@ -353,27 +362,32 @@ lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG)
     q.P = p->cfg.P; q.ld = p->cfg.ld; q.W = p->cfg.W; q.G = G;
     q.eta = eta; q.mu = p->cfg.momentum; q.wd = p->cfg.weight_decay;
     q.lamL = lamL; q.lamG = lamG;
-    if (p->cfg.flags & LSGD_PULL_UNSCALED_BY_ETA) {
+    if (unscaled && !comm) {
         if (lamL != 0.0f) q.lamL = lamL / eta;
         if (lamG != 0.0f) q.lamG = lamG / eta;
     }
     q.flags = p->cfg.flags;
-    bool any_pending = p->pending_global;
-    for (int j = 0; j < G; ++j) any_pending = any_pending || p->pending_local[(size_t)j];
-    q.use_refreshed = any_pending ? 1 : 0;
+    q.use_refreshed = any_pending(p) ? 1 : 0;
     q.clear_refreshed = 0;
     q.group_size = p->group_size;
+    q.comm_pull = comm ? 1 : 0;
     hipError_t e = launch_pull_update(q, p->st, p->stream);
-    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "pull_update: %s", hipGetErrorString(e));
-    // a refreshed leader whose term was active has now been captured (and kept, if Z exists)
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "%s: %s", comm ? "leader_pull" : "pull_update", hipGetErrorString(e));
+    // a refreshed leader whose term was active has now been captured (and kept, if Z exists);
+    // the communication pull captures every refreshed leader
     for (int j = 0; j < G; ++j) {
-        if (p->pending_local[(size_t)j] && lamL != 0.0f) p->z_valid[(size_t)j] = p->Z != nullptr;
+        if (p->pending_local[(size_t)j] && (comm || lamL != 0.0f)) p->z_valid[(size_t)j] = p->Z != nullptr;
         p->pending_local[(size_t)j] = 0;
     }
-    if (p->pending_global && lamG != 0.0f) p->z_valid[(size_t)G] = p->Z != nullptr;
+    if (p->pending_global && (comm || lamG != 0.0f)) p->z_valid[(size_t)G] = p->Z != nullptr;
     p->pending_global = false;
     if (!(p->cfg.flags & LSGD_WRITE_BF16_SHADOW)) p->shadow_valid = false;
     return LSGD_OK;
+}
+
+lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG)
+{
+    return do_pull(p, eta, lamL, lamG, (p->cfg.flags & LSGD_PULL_UNSCALED_BY_ETA) != 0, false);
 }
 
 } // namespace
@@ -419,6 +433,73 @@ lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, 
     st = do_select(pop, nullptr, refresh_local, refresh_global);
     if (st != LSGD_OK) return st;
     return do_pull(pop, eta, lambda_L, lambda_G);
+}
+
+lsgd_status lsgd_leader_pull(lsgd_population* pop, float lambda_L, float lambda_G)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    lsgd_status st = check_scalars(0.0f, lambda_L, lambda_G);
+    if (st != LSGD_OK) return st;
+    if (!any_pending(pop)) return fail(LSGD_ERR_STATE, "leader_pull: no leader was re-selected since the last update");
+    return do_pull(pop, 0.0f, lambda_L, lambda_G, false, true);
+}
+
+lsgd_status lsgd_step_alg1(lsgd_population* pop, const lsgd_batch* batch, float eta, float gamma_L, float gamma_G,
+                           float lambda_L, float lambda_G, int comm, const uint8_t* comm_local_mask)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    lsgd_status st = check_scalars(eta, gamma_L, gamma_G);
+    if (st != LSGD_OK) return st;
+    st = check_scalars(eta, lambda_L, lambda_G);
+    if (st != LSGD_OK) return st;
+    if (comm & ~(LSGD_COMM_LOCAL | LSGD_COMM_GLOBAL)) return fail(LSGD_ERR_INVALID_ARG, "step_alg1: unknown comm bits %d", comm);
+    if (!pop->Z) return fail(LSGD_ERR_STATE, "step_alg1 needs the z_snapshot buffer");
+    if ((gamma_L != 0.0f || gamma_G != 0.0f) && eta == 0.0f) return fail(LSGD_ERR_INVALID_ARG, "unscaled pulls need eta != 0");
+    st = check_grad_loss(pop, batch);
+    if (st != LSGD_OK) return st;
+    // the every-iteration pulls read kept copies (or leaders still pending from an explicit selection)
+    st = check_pull_state(pop, eta, gamma_L, gamma_G, nullptr, false, false);
+    if (st != LSGD_OK) return st;
+    const int G = pop->cfg.n_groups;
+    bool any_local = false;
+    if (comm & LSGD_COMM_LOCAL) {
+        for (int j = 0; j < G; ++j) any_local = any_local || !comm_local_mask || comm_local_mask[j];
+    }
+    st = do_grad_loss(pop, batch, nullptr);
+    if (st != LSGD_OK) return st;
+    st = do_pull(pop, eta, gamma_L, gamma_G, true, false);
+    if (st != LSGD_OK) return st;
+    if (!any_local && !(comm & LSGD_COMM_GLOBAL)) return LSGD_OK;
+    std::vector<uint8_t> none;
+    const uint8_t* mask = comm_local_mask;
+    if (!(comm & LSGD_COMM_LOCAL)) {
+        none.assign((size_t)G, 0);
+        mask = none.data();
+    }
+    st = do_select(pop, nullptr, mask, (comm & LSGD_COMM_GLOBAL) != 0);
+    if (st != LSGD_OK) return st;
+    return do_pull(pop, 0.0f, lambda_L, lambda_G, false, true);
+}
+
+lsgd_status lsgd_smooth_losses(lsgd_population* pop, float* window, int32_t K, int64_t t, const float* losses, float* out)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!window) return fail(LSGD_ERR_INVALID_ARG, "smooth_losses: window is NULL");
+    if (K <= 0 || K > 65536) return fail(LSGD_ERR_SHAPE, "smooth_losses: K = %d outside [1, 65536]", (int)K);
+    if (t < 0) return fail(LSGD_ERR_INVALID_ARG, "smooth_losses: t is negative");
+    hipError_t e = launch_smooth_losses(window, K, t, losses ? losses : pop->st.losses, pop->cfg.W,
+                                        out ? out : pop->st.losses, pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "smooth_losses: %s", hipGetErrorString(e));
+    return LSGD_OK;
+}
+
+lsgd_status lsgd_center(lsgd_population* pop, float* out)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!out) return fail(LSGD_ERR_INVALID_ARG, "center: out is NULL");
+    hipError_t e = launch_center(pop->x, pop->cfg.W, pop->cfg.P, pop->cfg.ld, out, pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "center: %s", hipGetErrorString(e));
+    return LSGD_OK;
 }
 
 lsgd_status lsgd_mc_pack_entries(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n_obs,

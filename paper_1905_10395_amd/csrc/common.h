@@ -48,8 +48,12 @@ struct PullParams {
     int use_refreshed;  // 0: treat every leader as kept (read Z)
     int clear_refreshed;
     int group_size;     // rows per group when all groups are equal, else 0
+    int comm_pull;      // 1: Algorithm 1's communication pull (no gradient, no momentum)
 };
 hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s);
+
+hipError_t launch_smooth_losses(float* window, int K, int64_t t, const float* losses, int W, float* out, hipStream_t s);
+hipError_t launch_center(const float* x, int W, int64_t P, int64_t ld, float* out, hipStream_t s);
 
 hipError_t launch_cast_shadow(const float* x, uint16_t* xb, int W, int64_t P, int64_t ld, hipStream_t s);
 

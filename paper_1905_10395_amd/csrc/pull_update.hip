@@ -61,9 +61,17 @@ struct Coef {
 
 // One parameter (or four, element-wise).  Written with plain operators so that
 // the compiler forms the fused multiply-adds itself.
-template <bool MOM, class V>
+// KIND 0: gradient step, 1: gradient step with momentum, 2: Algorithm 1's communication pull
+// (x <- x - cL (x - zl), then x <- x - cG (x - zg); no gradient, momentum untouched).
+template <int KIND, class V>
 __device__ __forceinline__ void update_vec(V& x, const V g, V& m, const V zl, const V zg, const Coef& c)
 {
+    constexpr bool MOM = KIND == 1;
+    if (KIND == 2) {
+        const V y = x - c.cL * (x - zl);
+        x = y - c.cG * (y - zg);
+        return;
+    }
     V d = g + c.wd * x;
     const V pull = c.cL * (x - zl) + c.cG * (x - zg);
     V step;
@@ -115,26 +123,26 @@ __device__ __forceinline__ Coef make_coef(const PullDev& a)
     return c;
 }
 
-template <int VEC, bool MOM>
+template <int VEC, int KIND>
 __device__ __forceinline__ void apply_row(const PullDev& a, int64_t o, typename Vec<VEC>::type xv, typename Vec<VEC>::type gv,
                                           typename Vec<VEC>::type mv, const typename Vec<VEC>::type zl,
                                           const typename Vec<VEC>::type zg, const Coef& c)
 {
     using V = typename Vec<VEC>::type;
-    update_vec<MOM, V>(xv, gv, mv, zl, zg, c);
+    update_vec<KIND, V>(xv, gv, mv, zl, zg, c);
     st_stream(a.x + o, xv);
-    if (MOM) st_stream(a.m + o, mv);
+    if (KIND == 1) st_stream(a.m + o, mv);
     if (a.xb) st_bf16(a.xb + o, xv);
 }
 
-template <int VEC, bool MOM>
+template <int VEC, int KIND>
 __device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename Vec<VEC>::type xv,
                                            const typename Vec<VEC>::type zl, const typename Vec<VEC>::type zg, const Coef& c)
 {
     using V = typename Vec<VEC>::type;
-    V gv = ld_stream<VEC>(a.g + o);
-    V mv = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
-    apply_row<VEC, MOM>(a, o, xv, gv, mv, zl, zg, c);
+    V gv = (KIND != 2) ? ld_stream<VEC>(a.g + o) : zero_of(V());
+    V mv = (KIND == 1) ? ld_stream<VEC>(a.m + o) : zero_of(V());
+    apply_row<VEC, KIND>(a, o, xv, gv, mv, zl, zg, c);
 }
 
 // Kernel 1: every row that nobody reads as a freshly selected leader.  One
@@ -146,7 +154,7 @@ __device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename
 // of the die that reads them instead of being fetched again for each row.
 constexpr int kChunkTiles = 1024;
 
-template <int VEC, bool MOM>
+template <int VEC, int KIND>
 __global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int64_t tiles, int tpc)
 {
     using V = typename Vec<VEC>::type;
@@ -159,7 +167,8 @@ __global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int6
     if (tile >= tiles) return;
     const int64_t col = a.col0 + (tile * kPullThreads + threadIdx.x) * VEC;
     if (col >= a.col1) return;
-    const bool pullG = a.lamG != 0.0f, pullL = a.lamL != 0.0f;
+    constexpr bool COMM = KIND == 2;       // communication pull: every re-selected leader is captured
+    bool pullG = COMM || a.lamG != 0.0f, pullL = COMM || a.lamL != 0.0f;
     const int j = a.group_size ? row / a.group_size : a.group_of[row];
     const int ll = pullL ? a.lead[j] : -1;
     const int gl = pullG ? a.glead[0] : -1;
@@ -167,18 +176,23 @@ __global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int6
     const bool freshG = pullG && a.use_refreshed && a.refreshed[a.G];
     // rows captured as leaders in this update are handled by pull_leaders_kernel afterwards
     if ((freshL && row == ll) || (freshG && row == gl)) return;
+    Coef c = make_coef<V>(a);
+    if (COMM) {                            // only leaders selected just now pull
+        if (!freshL) { c.cL = 0.0f; pullL = false; }
+        if (!freshG) { c.cG = 0.0f; pullG = false; }
+        if (c.cL == 0.0f && c.cG == 0.0f) return;
+    }
 
     const int64_t o = (int64_t)row * a.ld + col;
     V xv = ld_stream<VEC>(a.x + o);
     V zl = zero_of(V()), zg = zero_of(V());
     if (pullL) zl = ld_vec<VEC>((freshL ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
     if (pullG) zg = ld_vec<VEC>((freshG ? a.x + (int64_t)gl * a.ld : a.Z + (int64_t)a.G * a.ld) + col);
-    Coef c = make_coef<V>(a);
-    if (a.flags & LSGD_LEADER_EXEMPT) {
+    if (!COMM && (a.flags & LSGD_LEADER_EXEMPT)) {
         if (row == ll) c.cL = 0.0f;
         if (row == gl) c.cG = 0.0f;
     }
-    update_row<VEC, MOM>(a, o, xv, zl, zg, c);
+    update_row<VEC, KIND>(a, o, xv, zl, zg, c);
 }
 
 // Kernel 2 (runs after kernel 1): the rows that were captured as leaders.  A
@@ -187,17 +201,19 @@ __global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int6
 // row is updated at once (its local pull still sees its group's leader
 // untouched), then each re-selected local leader, whose pull to itself is
 // exactly zero.  Captured tiles are also written to the kept-copy buffer Z.
-template <int VEC, bool MOM>
+template <int VEC, int KIND>
 __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
 {
     using V = typename Vec<VEC>::type;
     const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
     if (col >= a.col1) return;
-    const bool pullG = a.lamG != 0.0f, pullL = a.lamL != 0.0f;
-    const bool exempt = (a.flags & LSGD_LEADER_EXEMPT) != 0;
+    constexpr bool COMM = KIND == 2;
+    const bool pullG = COMM ? a.refreshed[a.G] != 0 : a.lamG != 0.0f, pullL = COMM || a.lamL != 0.0f;
+    const bool exempt = !COMM && (a.flags & LSGD_LEADER_EXEMPT) != 0;
     const bool freshG = pullG && a.refreshed[a.G];
     const int gl = pullG ? a.glead[0] : -1;
     Coef c = make_coef<V>(a);
+    if (COMM && !freshG) c.cG = 0.0f;
 
     V zg = zero_of(V());
     if (pullG) zg = ld_vec<VEC>((freshG ? a.x + (int64_t)gl * a.ld : a.Z + (int64_t)a.G * a.ld) + col);
@@ -206,10 +222,14 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
         const int j = a.group_of[gl];
         const int ll = pullL ? a.lead[j] : -1;
         V zl = zero_of(V());
-        if (pullL) zl = (ll == gl) ? zg : ld_vec<VEC>((a.refreshed[j] ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
         Coef cg = c;
+        if (COMM && !a.refreshed[j]) cg.cL = 0.0f;       // its group did not communicate: no local pull
+        if (pullL && cg.cL != 0.0f)
+            zl = (ll == gl) ? zg : ld_vec<VEC>((a.refreshed[j] ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
+        else
+            cg.cL = 0.0f;
         if (exempt) { cg.cG = 0.0f; if (ll == gl) cg.cL = 0.0f; }
-        update_row<VEC, MOM>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);
+        update_row<VEC, KIND>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);
     }
     if (!pullL) return;
     // re-selected local leaders, four at a time so that their loads are all in flight together
@@ -232,8 +252,8 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
             if (u < cnt) {
                 const int64_t o = (int64_t)row[u] * a.ld + col;
                 xv[u] = ld_vec<VEC>(a.x + o);
-                gv[u] = ld_stream<VEC>(a.g + o);
-                mv[u] = MOM ? ld_stream<VEC>(a.m + o) : zero_of(V());
+                gv[u] = (KIND != 2) ? ld_stream<VEC>(a.g + o) : zero_of(V());
+                mv[u] = (KIND == 1) ? ld_stream<VEC>(a.m + o) : zero_of(V());
             }
         }
 #pragma unroll
@@ -243,13 +263,13 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
                 if (a.Z) st_vec(a.Z + (int64_t)grp[u] * a.ld + col, xv[u]);
                 Coef cl = c;
                 if (exempt) { cl.cL = 0.0f; if (row[u] == gl) cl.cG = 0.0f; }
-                apply_row<VEC, MOM>(a, o, xv[u], gv[u], mv[u], xv[u], zg, cl);
+                apply_row<VEC, KIND>(a, o, xv[u], gv[u], mv[u], xv[u], zg, cl);
             }
         }
     }
 }
 
-template <int VEC, bool MOM>
+template <int VEC, int KIND>
 static void launch_range(PullDev a, bool leaders, hipStream_t s)
 {
     const int64_t cols = a.col1 - a.col0;
@@ -265,11 +285,11 @@ static void launch_range(PullDev a, bool leaders, hipStream_t s)
         PullDev part = a;
         part.col0 = a.col0 + c0 * tpc * per_block;
         const int64_t part_tiles = (tiles - c0 * tpc) < nch * tpc ? (tiles - c0 * tpc) : nch * tpc;
-        hipLaunchKernelGGL((pull_rows_kernel<VEC, MOM>), dim3((unsigned)(nch * a.W * tpc)), dim3(kPullThreads), 0, s, part,
+        hipLaunchKernelGGL((pull_rows_kernel<VEC, KIND>), dim3((unsigned)(nch * a.W * tpc)), dim3(kPullThreads), 0, s, part,
                            part_tiles, tpc);
     }
     if (leaders)
-        hipLaunchKernelGGL((pull_leaders_kernel<VEC, MOM>), dim3((unsigned)tiles), dim3(kPullThreads), 0, s, a);
+        hipLaunchKernelGGL((pull_leaders_kernel<VEC, KIND>), dim3((unsigned)tiles), dim3(kPullThreads), 0, s, a);
 }
 
 hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s)
@@ -280,19 +300,20 @@ hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStr
     a.eta = p.eta; a.lamL = p.lamL; a.lamG = p.lamG; a.mu = p.mu; a.wd = p.wd;
     a.flags = p.flags; a.use_refreshed = p.use_refreshed; a.group_size = p.group_size;
     a.offsets = st.offsets; a.group_of = st.group_of; a.lead = st.lead; a.glead = st.glead; a.refreshed = st.refreshed;
-    const bool mom = p.mu != 0.0f;
-    const bool leaders = p.use_refreshed && (p.lamL != 0.0f || p.lamG != 0.0f);
+    const bool comm = p.comm_pull != 0;
+    const bool mom = !comm && p.mu != 0.0f;
+    const bool leaders = p.use_refreshed && (comm || p.lamL != 0.0f || p.lamG != 0.0f);
 
     auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-    const bool vec_ok = (p.ld % 4 == 0) && aligned16(p.x) && aligned16(p.g) && (!mom || aligned16(p.m)) &&
+    const bool vec_ok = (p.ld % 4 == 0) && aligned16(p.x) && (comm || aligned16(p.g)) && (!mom || aligned16(p.m)) &&
                         (!p.Z || aligned16(p.Z)) && (!p.xb || (reinterpret_cast<uintptr_t>(p.xb) & 7u) == 0);
     const int64_t P4 = vec_ok ? (p.P & ~(int64_t)3) : 0;
     // whole float4 columns, then the ragged tail (or everything) element-wise;
     // the two column ranges are disjoint, so their launches are independent
     a.col0 = 0; a.col1 = P4;
-    if (mom) launch_range<4, true>(a, leaders, s); else launch_range<4, false>(a, leaders, s);
+    if (comm) launch_range<4, 2>(a, leaders, s); else if (mom) launch_range<4, 1>(a, leaders, s); else launch_range<4, 0>(a, leaders, s);
     a.col0 = P4; a.col1 = p.P;
-    if (mom) launch_range<1, true>(a, leaders, s); else launch_range<1, false>(a, leaders, s);
+    if (comm) launch_range<1, 2>(a, leaders, s); else if (mom) launch_range<1, 1>(a, leaders, s); else launch_range<1, 0>(a, leaders, s);
     return hipGetLastError();
 }
 
