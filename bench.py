@@ -200,7 +200,7 @@ def run_c2(L, steps, warmup, data):
         "workload": f"matrix completion LSGD: 20000x20000 rank 32, 1% observed ({prob.n_obs}), W={W} in {G} groups, "
                     f"B={B}/worker/step, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps",
         "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
-        "roofline": {"kernel": "lsgd_grad_loss stage: mc_residual + mc_scan + mc_scatter + mc_reduce + mc_loss_finish kernels", "bound": "hbm", "achieved": ach,
+        "roofline": {"kernel": "lsgd_grad_loss stage: mc_prep + mc_side + mc_loss_finish kernels", "bound": "hbm", "achieved": ach,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": grad_bytes, "ms_per_launch": ms_grad},
         "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},

@@ -111,19 +111,27 @@ __global__ __launch_bounds__(256) void mc_loss_finish_kernel(const float* __rest
 }
 
 // ------------------------------------------------------------------------------------------
-// Binned path (r % 4 == 0, 16-byte aligned rows): no global floating-point atomics.
+// Binned path (r % 4 == 0, 16-byte aligned rows): no global floating-point atomics, and each
+// factor row an entry touches is gathered once per side.
 // Factor rows are grouped in bins of 64 consecutive rows (U bins, then V bins).
-//   1. residual kernel (1024 entries per workgroup): fetches each entry's (a, b, M), computes
-//      e_k with a lane group per entry, and ranks the entries of the workgroup inside their U bin
-//      and V bin with LDS counters; writes the workgroup's bin histogram.
-//   2. scan kernel: per worker, bin totals -> bin starts, and the start of every workgroup's
-//      share inside each bin.
-//   3. scatter kernel: entry -> record (row inside the bin, other factor's row, e_k) at
-//      bin start + workgroup share + rank, once for the U side and once for the V side.
-//   4. reduce kernel: one workgroup per (worker, bin) sorts the bin's records by row in LDS, then
-//      each lane group sums e_k * other_row over the records of its rows in registers and writes
-//      the gradient row once, scaled by 2c; rows without entries come out as zeros, so there is
-//      no separate zero fill.
+//   1. prepare kernel (1024 threads, E = 1024..4096 entries per workgroup): fetches each entry's
+//      (a, b, M), ranks the workgroup's entries inside their U bin and V bin with LDS counters,
+//      scans the counters, and writes every entry twice into the workgroup's own region of 2E
+//      records: as (row of a inside its bin, b, M) grouped by U bin, and as (row of b inside its
+//      bin, a, M) grouped by V bin, plus the table of where each bin starts in that region.  No
+//      factor row is read here, and no pass over all workgroups is needed: a bin's records are
+//      the union of one short segment per workgroup.
+//   2. side kernel: one workgroup per (worker, bin), U and V bins alike, in one launch.  It
+//      collects the bin's segments and sorts the records by row in LDS; a lane group takes its own
+//      row from an LDS copy of the bin's rows, gathers the other factor's row for each record,
+//      forms e = <U[a], V[b]> - M and adds e times the gathered row to its row's gradient.  Both
+//      sides form e with the same lane partition and reduction tree, so they get the same bits.
+//      U bins also sum e^2 (double per lane, fixed tree over the workgroup).
+//   3. loss: c * the U bins' sums, added in bin order in double.
+// Gradient rows are written once, scaled by 2c; rows without entries come out as zeros, so
+// there is no separate zero fill.  The order of a row's records follows LDS rank order, so the
+// last bits of a gradient row (fp32 sums) can differ between runs; the loss is summed in double,
+// where a different order changes the rounded fp32 result only in freak cases.
 // Workgroups of one worker are numbered so that they land on one die (workgroup id modulo 8),
 // which keeps the worker's factors, 5 MB at rank 32, in that die's L2.  This placement only
 // affects speed, never results.
@@ -131,19 +139,15 @@ __global__ __launch_bounds__(256) void mc_loss_finish_kernel(const float* __rest
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kBinRows = 64;          // factor rows per bin
-constexpr int kResEntries = 1024;     // entries per workgroup in the residual kernel
+constexpr int kPrepThreads = 1024;    // threads per workgroup in the prepare kernel
 constexpr int kMaxBins = 8192;        // LDS histogram capacity (U bins + V bins)
 constexpr int kXcd = 8;
 
 struct McBinned {
-    int32_t* hist;   // [W][nblk][nbins] per-workgroup bin counts, then the bin's records before this workgroup
-    int32_t* bstart; // [W][nbins+1] bin starts
-    int32_t* ea;     // [W][nb] a_k
-    int32_t* eb;     // [W][nb] b_k
-    float* ee;       // [W][nb] e_k
-    uint32_t* rk;    // [W][nb] rank in U bin (low 16 bits) | rank in V bin (high 16 bits), within the workgroup
-    int2* rec;       // [W][2*nb] (row-in-bin << 26 | other row, e bits): U bins then V bins
-    int nbinsU, nbins, nblk;
+    int32_t* segs;   // [W][nblk][nbins+1] first record of each bin inside the workgroup's region
+                     // (U bins fill [0, count), V bins [count, 2 count); entry nbins = 2 count)
+    int2* rec;       // [W][nblk][2E] (row-in-bin << 26 | other factor's row, M bits)
+    int nbinsU, nbins, nblk, E;
 };
 
 // maps a linear workgroup id to (worker, chunk) with all chunks of a worker on the same die
@@ -156,226 +160,223 @@ __device__ __forceinline__ bool xcd_map(int64_t id, int W, int nchunk, int& w, i
     return w < W;
 }
 
-template <int LPE>
-__global__ __launch_bounds__(kResEntries) void mc_residual_kernel(
-    const float* __restrict__ x, int64_t ld, int m, int n, int r, const int32_t* __restrict__ rows,
-    const int32_t* __restrict__ cols, const float* __restrict__ vals, const int32_t* __restrict__ batch_idx,
-    int64_t nb, McBinned S, float* __restrict__ partials, int W, const lsgd_mc_entry* __restrict__ entries)
+template <int EPT>
+__global__ __launch_bounds__(kPrepThreads) void mc_prep_kernel(
+    const int32_t* __restrict__ rows, const int32_t* __restrict__ cols, const float* __restrict__ vals,
+    const int32_t* __restrict__ batch_idx, int64_t nb, McBinned S, const lsgd_mc_entry* __restrict__ entries)
 {
-    int w, blk;
-    if (!xcd_map(blockIdx.x, W, S.nblk, w, blk)) return;
-    const float* U = x + (int64_t)w * ld;
-    const float* V = U + (int64_t)m * r;
-    extern __shared__ int lhist[];                 // [nbins]
-    __shared__ int sa[kResEntries], sb[kResEntries];
-    __shared__ float sv[kResEntries];
-    __shared__ float red[kResEntries / 64];
-    const int t = threadIdx.x;
-    const int64_t k0 = (int64_t)blk * kResEntries;
-    const int cnt_here = (int)((nb - k0 < kResEntries) ? nb - k0 : kResEntries);
-    for (int i = t; i < S.nbins; i += kResEntries) lhist[i] = 0;
-    // phase 1: thread t fetches entry t's (a, b, M): all index chasing of the workgroup is in flight at once
-    if (t < cnt_here) {
-        const int64_t s = batch_idx ? (int64_t)batch_idx[(int64_t)w * nb + k0 + t] : k0 + t;
-        int a, b;
-        float mv;
-        fetch_entry(entries, rows, cols, vals, s, a, b, mv);
-        sa[t] = a; sb[t] = b; sv[t] = mv;
+    constexpr int E = EPT * kPrepThreads;
+    const int w = blockIdx.y, blk = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    extern __shared__ int lhist[];                 // [nbins + 1]
+    __shared__ int wsum[kPrepThreads / 64];
+    for (int i = t; i <= S.nbins; i += kPrepThreads) lhist[i] = 0;
+    const int64_t k0 = (int64_t)blk * E;
+    const int cnt_here = (int)((nb - k0 < E) ? nb - k0 : E);
+    // every index chase of the workgroup is in flight at once
+    int64_t src[EPT];
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+        const int i = u * kPrepThreads + t;
+        src[u] = (i < cnt_here) ? (batch_idx ? (int64_t)batch_idx[(int64_t)w * nb + k0 + i] : k0 + i) : 0;
+    }
+    int a[EPT], b[EPT];
+    float mv[EPT];
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+        a[u] = b[u] = 0; mv[u] = 0.f;
+        if (u * kPrepThreads + t < cnt_here) fetch_entry(entries, rows, cols, vals, src[u], a[u], b[u], mv[u]);
     }
     __syncthreads();
-    // phase 2: LPE lanes per entry, two entries per lane group in flight; sv[] becomes e_k
-    const int sub = t / LPE, q0 = t % LPE;
-    constexpr int kSubs = kResEntries / LPE;
-    const int r4 = r >> 2;
-    for (int e0 = sub; e0 < cnt_here; e0 += 2 * kSubs) {
-        const int e1 = e0 + kSubs;
-        const bool two = e1 < cnt_here;
-        const v4f* ua0 = reinterpret_cast<const v4f*>(U + (int64_t)sa[e0] * r);
-        const v4f* vb0 = reinterpret_cast<const v4f*>(V + (int64_t)sb[e0] * r);
-        const v4f* ua1 = reinterpret_cast<const v4f*>(U + (int64_t)sa[two ? e1 : e0] * r);
-        const v4f* vb1 = reinterpret_cast<const v4f*>(V + (int64_t)sb[two ? e1 : e0] * r);
-        float d0 = 0.f, d1 = 0.f;
-        for (int q = q0; q < r4; q += LPE) {
-            const v4f u0 = ua0[q], v0 = vb0[q], u1 = ua1[q], v1 = vb1[q];
-            d0 += u0.x * v0.x + u0.y * v0.y + u0.z * v0.z + u0.w * v0.w;
-            d1 += u1.x * v1.x + u1.y * v1.y + u1.z * v1.z + u1.w * v1.w;
-        }
+    int ru[EPT], rv[EPT];
 #pragma unroll
-        for (int d = 1; d < LPE; d <<= 1) { d0 += __shfl_xor(d0, d, LPE); d1 += __shfl_xor(d1, d, LPE); }
-        if (q0 == 0) {
-            sv[e0] = d0 - sv[e0];
-            if (two) sv[e1] = d1 - sv[e1];
+    for (int u = 0; u < EPT; ++u) {
+        if (u * kPrepThreads + t < cnt_here) {
+            ru[u] = atomicAdd(&lhist[a[u] / kBinRows], 1);
+            rv[u] = atomicAdd(&lhist[S.nbinsU + b[u] / kBinRows], 1);
         }
     }
     __syncthreads();
-    // phase 3: thread t records entry t (coalesced stores) and takes its ranks from the LDS counters
-    float sq = 0.f;
-    if (t < cnt_here) {
-        const float e = sv[t];
-        sq = e * e;
-        const int a = sa[t], b = sb[t];
-        const int64_t o = (int64_t)w * nb + k0 + t;
-        const uint32_t ru = (uint32_t)atomicAdd(&lhist[a / kBinRows], 1);
-        const uint32_t rv = (uint32_t)atomicAdd(&lhist[S.nbinsU + b / kBinRows], 1);
-        S.ea[o] = a; S.eb[o] = b; S.ee[o] = e;
-        S.rk[o] = ru | (rv << 16);
+    // exclusive scan of the counters in place: thread t owns `per` consecutive bins
+    const int per = (S.nbins + kPrepThreads - 1) / kPrepThreads;     // <= kMaxBins / 1024
+    int loc[kMaxBins / kPrepThreads];
+    int tot = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxBins / kPrepThreads; ++q) {
+        const int i = t * per + q;
+        loc[q] = (q < per && i < S.nbins) ? lhist[i] : 0;
+        tot += loc[q];
     }
-    // squared-error partial of the workgroup, in a fixed order
+    int inc = tot;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) sq += __shfl_xor(sq, d, 64);
-    if ((t & 63) == 0) red[t >> 6] = sq;
+    for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(inc, d, 64); if (lane >= d) inc += v; }
+    if (lane == 63) wsum[wv] = inc;
     __syncthreads();
-    if (t == 0) {
-        float tot = 0.f;
-        for (int i = 0; i < kResEntries / 64; ++i) tot += red[i];
-        partials[(int64_t)w * S.nblk + blk] = tot;
+    int run = inc - tot;
+    for (int q = 0; q < wv; ++q) run += wsum[q];
+#pragma unroll
+    for (int q = 0; q < kMaxBins / kPrepThreads; ++q) {
+        const int i = t * per + q;
+        if (q < per && i < S.nbins) { lhist[i] = run; run += loc[q]; }
     }
-    int32_t* gh = S.hist + ((int64_t)w * S.nblk + blk) * S.nbins;
-    for (int i = t; i < S.nbins; i += kResEntries) gh[i] = lhist[i];
-}
-
-// One workgroup per worker.  Thread per bin: walks the bin's column of the histogram matrix once
-// (coalesced across bins, sixteen loads in flight), replacing each workgroup's count by the number of
-// the bin's records that precede it; then an exclusive scan of the bin totals gives the bin starts.
-__global__ __launch_bounds__(1024) void mc_scan_kernel(McBinned S)
-{
-    const int w = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
-    int32_t* hist = S.hist + (int64_t)w * S.nblk * S.nbins;
-    int32_t* bstart = S.bstart + (int64_t)w * (S.nbins + 1);
-    __shared__ int wsum[16];
-    __shared__ int carry_s;
-    if (t == 0) carry_s = 0;
+    if (t == 0) lhist[S.nbins] = 2 * cnt_here;
     __syncthreads();
-    for (int base = 0; base < S.nbins; base += 1024) {
-        const int bin = base + t;
-        int total = 0;
-        if (bin < S.nbins) {
-            for (int b0 = 0; b0 < S.nblk; b0 += 16) {
-                int c[16];
+    int32_t* seg = S.segs + ((int64_t)w * S.nblk + blk) * (S.nbins + 1);
+    for (int i = t; i <= S.nbins; i += kPrepThreads) seg[i] = lhist[i];
+    int2* rec = S.rec + ((int64_t)w * S.nblk + blk) * (2 * E);
 #pragma unroll
-                for (int q = 0; q < 16; ++q) c[q] = (b0 + q < S.nblk) ? hist[(int64_t)(b0 + q) * S.nbins + bin] : 0;
-#pragma unroll
-                for (int q = 0; q < 16; ++q) {
-                    if (b0 + q < S.nblk) hist[(int64_t)(b0 + q) * S.nbins + bin] = total;
-                    total += c[q];
-                }
-            }
+    for (int u = 0; u < EPT; ++u) {
+        if (u * kPrepThreads + t < cnt_here) {
+            const int mb = __float_as_int(mv[u]);
+            rec[lhist[a[u] / kBinRows] + ru[u]] = make_int2(((a[u] % kBinRows) << 26) | b[u], mb);
+            rec[lhist[S.nbinsU + b[u] / kBinRows] + rv[u]] = make_int2(((b[u] % kBinRows) << 26) | a[u], mb);
         }
-        int inc = total;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(inc, d, 64); if (lane >= d) inc += v; }
-        if (lane == 63) wsum[wv] = inc;
-        __syncthreads();
-        int before = carry_s;
-        for (int q = 0; q < wv; ++q) before += wsum[q];
-        if (bin < S.nbins) bstart[bin] = before + inc - total;
-        __syncthreads();
-        if (t == 1023) carry_s = before + inc;
-        __syncthreads();
     }
-    if (t == 0) bstart[S.nbins] = carry_s;
 }
 
-__global__ __launch_bounds__(256) void mc_scatter_kernel(McBinned S, int64_t nb)
-{
-    const int w = blockIdx.y;
-    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (k >= nb) return;
-    const int blk = (int)(k / kResEntries);
-    const int32_t* share = S.hist + ((int64_t)w * S.nblk + blk) * S.nbins;
-    const int64_t o = (int64_t)w * nb + k;
-    const int a = S.ea[o], b = S.eb[o];
-    const int eb = __float_as_int(S.ee[o]);
-    const uint32_t rk = S.rk[o];
-    int2* rec = S.rec + (int64_t)w * 2 * nb;
-    const int32_t* bstart = S.bstart + (int64_t)w * (S.nbins + 1);
-    const int bu = a / kBinRows, bv = S.nbinsU + b / kBinRows;
-    rec[bstart[bu] + share[bu] + (int)(rk & 0xFFFFu)] = make_int2(((a % kBinRows) << 26) | b, eb);
-    rec[bstart[bv] + share[bv] + (int)(rk >> 16)] = make_int2(((b % kBinRows) << 26) | a, eb);
-}
-
-// One workgroup per (worker, bin).  The bin's records are staged in LDS and counting-sorted by their
-// row inside the bin (64 integer LDS counters), so that each lane group owns whole rows: it walks the
-// row's records, four gathers of the other factor's rows in flight, accumulates in registers and writes
-// the gradient row once (scaled by 2c).  Rows without records are written as zeros.
-constexpr int kRedCap = 2048;                     // records staged per pass
+// One workgroup per (worker, bin).  The bin's records (one segment per prepare workgroup) are
+// staged in LDS and counting-sorted by their row inside the bin (64 integer LDS counters), so that
+// each lane group owns whole rows: it walks the row's records, four gathers of the other factor's
+// rows in flight, forms each record's residual against its own row, accumulates in registers and
+// writes the gradient row once (scaled by 2c).  Rows without records are written as zeros.
+constexpr int kSideThreads = 256;
+constexpr int kRedCap = 1024;                     // records staged per pass
+constexpr int kSegCap = kSideThreads;             // segments collected per round
 
 template <int LPE>
-__global__ __launch_bounds__(kMcThreads) void mc_reduce_kernel(const float* __restrict__ x, float* __restrict__ g, int64_t ld,
-                                                               int m, int n, int r, McBinned S, int64_t nb, float two_c, int W)
+__global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __restrict__ x, float* __restrict__ g, int64_t ld,
+                                                             int m, int n, int r, McBinned S, float two_c,
+                                                             float* __restrict__ partials, int W)
 {
-    constexpr int kSubs = kMcThreads / LPE;                          // lane groups per workgroup
+    constexpr int kSubs = kSideThreads / LPE;                          // lane groups per workgroup
     constexpr int RPG = (kBinRows + kSubs - 1) / kSubs;              // rows per lane group
-    constexpr int PER = kRedCap / kMcThreads;                        // records per thread and pass
-    int w, bin;
-    if (!xcd_map(blockIdx.x, W, S.nbins, w, bin)) return;
+    constexpr int PER = kRedCap / kSideThreads;                        // records per thread and pass
+    int w, gbin;
+    if (!xcd_map(blockIdx.x, W, S.nbins, w, gbin)) return;
+    extern __shared__ v4f tile[];                                     // the bin's own rows [64][r]
     __shared__ int2 sorted[kRedCap];
     __shared__ int cnt[kBinRows], start[kBinRows + 1];
-    const int t = threadIdx.x;
-    const bool uside = bin < S.nbinsU;
-    const int row0 = (uside ? bin : bin - S.nbinsU) * kBinRows;       // first factor row of the bin
+    __shared__ int segoff[kSegCap + 1], segbase[kSegCap], wtot[kSideThreads / 64];
+    __shared__ double sqred[kSideThreads / 64];
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+    const bool uside = gbin < S.nbinsU;
+    const int row0 = (uside ? gbin : gbin - S.nbinsU) * kBinRows;     // first factor row of the bin
     const int nrows = uside ? m : n;
     const float* xw = x + (int64_t)w * ld;
-    const float* other = uside ? xw + (int64_t)m * r : xw;             // U rows gather V rows and vice versa
-    const int2* rec = S.rec + (int64_t)w * 2 * nb;
-    const int32_t* bstart = S.bstart + (int64_t)w * (S.nbins + 1);
-    const int j0 = bstart[bin], j1 = bstart[bin + 1];
+    const float* own = uside ? xw : xw + (int64_t)m * r;
+    const float* other = uside ? xw + (int64_t)m * r : xw;            // U rows gather V rows and vice versa
+    const int r4 = r >> 2;
+    {
+        const int live = (nrows - row0 < kBinRows ? nrows - row0 : kBinRows) * r4;
+        const v4f* src = reinterpret_cast<const v4f*>(own + (int64_t)row0 * r);
+        for (int i = t; i < live; i += kSideThreads) tile[i] = src[i];
+    }
+    const int2* rec = S.rec + (int64_t)w * S.nblk * (2 * S.E);
+    const int32_t* segs = S.segs + (int64_t)w * S.nblk * (S.nbins + 1) + gbin;
     const int sub = t / LPE, q0 = t % LPE;
-    const bool lane_live = q0 < (r >> 2);
+    const bool lane_live = q0 < r4;
     v4f acc[RPG];
 #pragma unroll
     for (int i = 0; i < RPG; ++i) acc[i] = (v4f)(0.f);
+    double sq = 0.0;
 
-    for (int c0 = j0; c0 < j1; c0 += kRedCap) {
-        const int nrec = (j1 - c0 < kRedCap) ? j1 - c0 : kRedCap;
-        if (t < kBinRows) cnt[t] = 0;
-        __syncthreads();
-        int2 mine[PER];
-        int rank[PER];
-#pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int i = t + u * kMcThreads;
-            if (i < nrec) {
-                mine[u] = rec[c0 + i];
-                rank[u] = atomicAdd(&cnt[(uint32_t)mine[u].x >> 26], 1);
-            }
+    for (int blk0 = 0; blk0 < S.nblk; blk0 += kSegCap) {
+        const int nseg = (S.nblk - blk0 < kSegCap) ? S.nblk - blk0 : kSegCap;
+        // this round's segments: thread t takes segment t, counts are scanned into segoff
+        int c = 0;
+        if (t < nseg) {
+            const int blk = blk0 + t;
+            const int32_t* sp = segs + (int64_t)blk * (S.nbins + 1);
+            const int s0 = sp[0];
+            c = sp[1] - s0;
+            segbase[t] = blk * (2 * S.E) + s0;
         }
+        int inc = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(inc, d, 64); if (lane >= d) inc += v; }
+        if (lane == 63) wtot[wv] = inc;
         __syncthreads();
-        if (t < 64) {                                                 // exclusive scan of the 64 row counts
-            const int c = cnt[t];
-            int inc = c;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(inc, d, 64); if (t >= d) inc += v; }
-            start[t] = inc - c;
-            if (t == 63) start[64] = inc;
-        }
+        int before = 0;
+        for (int q = 0; q < wv; ++q) before += wtot[q];
+        segoff[t + 1] = before + inc;
+        if (t == 0) segoff[0] = 0;
         __syncthreads();
+        const int total = segoff[kSideThreads];
+
+        for (int c0 = 0; c0 < total; c0 += kRedCap) {
+            const int nrec = (total - c0 < kRedCap) ? total - c0 : kRedCap;
+            if (t < kBinRows) cnt[t] = 0;
+            __syncthreads();
+            int2 mine[PER];
+            int rank[PER];
 #pragma unroll
-        for (int u = 0; u < PER; ++u) {
-            const int i = t + u * kMcThreads;
-            if (i < nrec) sorted[start[(uint32_t)mine[u].x >> 26] + rank[u]] = mine[u];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < RPG; ++i) {
-            const int row = sub + i * kSubs;
-            if (row < kBinRows && lane_live) {
-                const int s0 = start[row], s1 = start[row + 1];
-                for (int sidx = s0; sidx < s1; sidx += 4) {
-                    int2 rc[4];
-                    v4f ov[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) rc[u] = sorted[(sidx + u < s1) ? sidx + u : sidx];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        ov[u] = reinterpret_cast<const v4f*>(other + (int64_t)(rc[u].x & 0x3FFFFFF) * r)[q0];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        if (sidx + u < s1) acc[i] += __int_as_float(rc[u].y) * ov[u];
+            for (int u = 0; u < PER; ++u) {
+                const int i = t + u * kSideThreads;
+                if (i < nrec) {
+                    // segment holding record c0 + i: the s with segoff[s] <= c0 + i < segoff[s + 1]
+                    const int key = c0 + i;
+                    int lo = 0, hi = nseg;
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (segoff[mid] <= key) lo = mid; else hi = mid;
+                    }
+                    mine[u] = rec[segbase[lo] + (key - segoff[lo])];
+                    rank[u] = atomicAdd(&cnt[(uint32_t)mine[u].x >> 26], 1);
                 }
             }
+            __syncthreads();
+            if (t < 64) {                                             // exclusive scan of the 64 row counts
+                const int cc = cnt[t];
+                int in2 = cc;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(in2, d, 64); if (t >= d) in2 += v; }
+                start[t] = in2 - cc;
+                if (t == 63) start[64] = in2;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int i = t + u * kSideThreads;
+                if (i < nrec) sorted[start[(uint32_t)mine[u].x >> 26] + rank[u]] = mine[u];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < RPG; ++i) {
+                const int row = sub + i * kSubs;
+                if (row < kBinRows) {
+                    const int s0 = start[row], s1 = start[row + 1];
+                    v4f mine_row = (v4f)(0.f);
+                    if (s0 < s1 && lane_live) mine_row = tile[row * r4 + q0];
+                    for (int sidx = s0; sidx < s1; sidx += 4) {
+                        int2 rc[4];
+                        v4f ov[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) rc[u] = sorted[(sidx + u < s1) ? sidx + u : sidx];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            ov[u] = (lane_live && sidx + u < s1)
+                                        ? reinterpret_cast<const v4f*>(other + (int64_t)(rc[u].x & 0x3FFFFFF) * r)[q0] : (v4f)(0.f);
+                        float d[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            d[u] = mine_row.x * ov[u].x + mine_row.y * ov[u].y + mine_row.z * ov[u].z + mine_row.w * ov[u].w;
+#pragma unroll
+                        for (int sh = 1; sh < LPE; sh <<= 1) {
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) d[u] += __shfl_xor(d[u], sh, LPE);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            if (sidx + u < s1) {
+                                const float e = d[u] - __int_as_float(rc[u].y);
+                                acc[i] += e * ov[u];
+                                if (q0 == 0) sq += (double)e * (double)e;
+                            }
+                        }
+                    }
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
     }
     float* out = g + (int64_t)w * ld + (uside ? (int64_t)0 : (int64_t)m * r) + (int64_t)row0 * r;
 #pragma unroll
@@ -383,6 +384,17 @@ __global__ __launch_bounds__(kMcThreads) void mc_reduce_kernel(const float* __re
         const int row = sub + i * kSubs;
         if (row < kBinRows && row0 + row < nrows && lane_live)
             reinterpret_cast<v4f*>(out + (int64_t)row * r)[q0] = two_c * acc[i];
+    }
+    if (uside) {                                                      // sum of squared residuals of this U bin
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) sq += __shfl_xor(sq, d, 64);
+        if (lane == 0) sqred[wv] = sq;
+        __syncthreads();
+        if (t == 0) {
+            double tot = 0.0;
+            for (int q = 0; q < kSideThreads / 64; ++q) tot += sqred[q];
+            partials[(int64_t)w * S.nbinsU + gbin] = (float)tot;
+        }
     }
 }
 
@@ -416,27 +428,43 @@ static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 static int mc_bins_u(const lsgd_mc_batch& b) { return (b.m + kBinRows - 1) / kBinRows; }
 static int mc_bins(const lsgd_mc_batch& b) { return mc_bins_u(b) + (b.n + kBinRows - 1) / kBinRows; }
-static int mc_res_blocks(const lsgd_mc_batch& b) { return (int)((mc_entries(b) + kResEntries - 1) / kResEntries); }
-
-static bool mc_binned_ok(const lsgd_mc_batch& b)
+// entries per prepare workgroup: as many as keeps at least ~2 workgroups per compute unit busy,
+// more when the segment table would otherwise outgrow its bound
+static int mc_ept(int W, const lsgd_mc_batch& b)
 {
     const int64_t nb = mc_entries(b);
-    return b.r % 4 == 0 && nb > 0 && nb < ((int64_t)1 << 30) && mc_bins(b) <= kMaxBins && b.m < (1 << 26) && b.n < (1 << 26) &&
-           (size_t)kBinRows * b.r * 4 <= 64 * 1024 && (int64_t)mc_res_blocks(b) * mc_bins(b) <= ((int64_t)1 << 22);
+    int ept = 4;
+    while (ept > 1 && (int64_t)W * ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) < 512) ept >>= 1;
+    while (ept < 4 && ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) * (mc_bins(b) + 1) > ((int64_t)1 << 22))
+        ept <<= 1;
+    return ept;
+}
+static int mc_prep_blocks(int W, const lsgd_mc_batch& b)
+{
+    const int64_t E = (int64_t)mc_ept(W, b) * kPrepThreads;
+    return (int)((mc_entries(b) + E - 1) / E);
+}
+static bool mc_binned_ok(int W, const lsgd_mc_batch& b)
+{
+    const int64_t nb = mc_entries(b);
+    if (!(b.r % 4 == 0 && nb > 0 && nb < ((int64_t)1 << 30) && mc_bins(b) <= kMaxBins && b.m < (1 << 26) && b.n < (1 << 26) &&
+          (size_t)kBinRows * b.r * 4 <= 64 * 1024))
+        return false;
+    return (int64_t)mc_prep_blocks(W, b) * (mc_bins(b) + 1) <= ((int64_t)1 << 22);
 }
 
 size_t mc_partials(int W, const lsgd_mc_batch& b)
 {
-    const int64_t nblk = (mc_entries(b) + kMcEntriesPerBlock - 1) / kMcEntriesPerBlock;
+    int64_t nblk = (mc_entries(b) + kMcEntriesPerBlock - 1) / kMcEntriesPerBlock;   // general path: one per workgroup
+    if (nblk < mc_bins_u(b)) nblk = mc_bins_u(b);                                  // binned path: one per U bin
     return (size_t)W * (size_t)(nblk > 0 ? nblk : 1);
 }
 
 size_t mc_scratch_bytes(int W, const lsgd_mc_batch& b)
 {
-    if (!mc_binned_ok(b)) return 0;
-    const size_t nb = (size_t)mc_entries(b);
-    return up256((size_t)W * mc_res_blocks(b) * mc_bins(b) * 4) + up256((size_t)W * (mc_bins(b) + 1) * 4) +
-           4 * up256((size_t)W * nb * 4) + up256((size_t)W * 2 * nb * 8);
+    if (!mc_binned_ok(W, b)) return 0;
+    const size_t slots = (size_t)mc_prep_blocks(W, b) * mc_ept(W, b) * kPrepThreads;
+    return up256((size_t)W * mc_prep_blocks(W, b) * (mc_bins(b) + 1) * 4) + up256((size_t)W * 2 * slots * 8);
 }
 
 template <int LPE>
@@ -444,12 +472,16 @@ static void launch_binned(const float* x, float* g, int W, int64_t ld, const lsg
                           const McBinned& S, float* partials, hipStream_t s)
 {
     const int rounds = (W + kXcd - 1) / kXcd;
-    hipLaunchKernelGGL((mc_residual_kernel<LPE>), dim3((unsigned)((int64_t)rounds * kXcd * S.nblk)), dim3(kResEntries),
-                       (size_t)S.nbins * 4, s, x, ld, b.m, b.n, b.r, b.rows, b.cols, b.vals, b.batch_idx, nb, S, partials, W, b.entries);
-    hipLaunchKernelGGL(mc_scan_kernel, dim3((unsigned)W), dim3(1024), 0, s, S);
-    hipLaunchKernelGGL(mc_scatter_kernel, dim3((unsigned)((nb + 255) / 256), (unsigned)W), dim3(256), 0, s, S, nb);
-    hipLaunchKernelGGL((mc_reduce_kernel<LPE>), dim3((unsigned)((int64_t)rounds * kXcd * S.nbins)), dim3(kMcThreads),
-                       0, s, x, g, ld, b.m, b.n, b.r, S, nb, 2.0f * b.c, W);
+    const dim3 pgrid((unsigned)S.nblk, (unsigned)W);
+    const size_t plds = (size_t)(S.nbins + 1) * 4;
+    if (S.E == kPrepThreads)
+        hipLaunchKernelGGL((mc_prep_kernel<1>), pgrid, dim3(kPrepThreads), plds, s, b.rows, b.cols, b.vals, b.batch_idx, nb, S, b.entries);
+    else if (S.E == 2 * kPrepThreads)
+        hipLaunchKernelGGL((mc_prep_kernel<2>), pgrid, dim3(kPrepThreads), plds, s, b.rows, b.cols, b.vals, b.batch_idx, nb, S, b.entries);
+    else
+        hipLaunchKernelGGL((mc_prep_kernel<4>), pgrid, dim3(kPrepThreads), plds, s, b.rows, b.cols, b.vals, b.batch_idx, nb, S, b.entries);
+    hipLaunchKernelGGL((mc_side_kernel<LPE>), dim3((unsigned)((int64_t)rounds * kXcd * S.nbins)), dim3(kSideThreads),
+                       (size_t)kBinRows * b.r * 4, s, x, g, ld, b.m, b.n, b.r, S, 2.0f * b.c, partials, W);
 }
 
 hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, int64_t P, int64_t ld,
@@ -457,18 +489,12 @@ hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, i
 {
     const int64_t nb = mc_entries(b);
     const bool aligned = (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && (reinterpret_cast<uintptr_t>(g) & 15u) == 0 && ld % 4 == 0;
-    const bool binned = mc_binned_ok(b) && aligned && st.scratch_bytes >= mc_scratch_bytes(W, b);
+    const bool binned = mc_binned_ok(W, b) && aligned && st.scratch_bytes >= mc_scratch_bytes(W, b);
     if (binned) {
         McBinned S;
-        S.nbinsU = mc_bins_u(b); S.nbins = mc_bins(b); S.nblk = mc_res_blocks(b);
+        S.nbinsU = mc_bins_u(b); S.nbins = mc_bins(b); S.nblk = mc_prep_blocks(W, b); S.E = mc_ept(W, b) * kPrepThreads;
         char* p = st.scratch;
-        const size_t nbw = up256((size_t)W * (size_t)nb * 4);
-        S.hist = reinterpret_cast<int32_t*>(p); p += up256((size_t)W * S.nblk * S.nbins * 4);
-        S.bstart = reinterpret_cast<int32_t*>(p); p += up256((size_t)W * (S.nbins + 1) * 4);
-        S.ea = reinterpret_cast<int32_t*>(p); p += nbw;
-        S.eb = reinterpret_cast<int32_t*>(p); p += nbw;
-        S.ee = reinterpret_cast<float*>(p); p += nbw;
-        S.rk = reinterpret_cast<uint32_t*>(p); p += nbw;
+        S.segs = reinterpret_cast<int32_t*>(p); p += up256((size_t)W * S.nblk * (S.nbins + 1) * 4);
         S.rec = reinterpret_cast<int2*>(p);
         const int r4 = b.r / 4;
         if (r4 <= 1) launch_binned<1>(x, g, W, ld, b, nb, S, st.partials, s);
@@ -480,7 +506,7 @@ hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, i
         else launch_binned<64>(x, g, W, ld, b, nb, S, st.partials, s);
         if (ld > P)
             hipLaunchKernelGGL(mc_zero_pad_kernel, dim3((unsigned)((ld - P + 255) / 256), (unsigned)W), dim3(256), 0, s, g, P, ld);
-        hipLaunchKernelGGL(mc_loss_finish_kernel, dim3((unsigned)W), dim3(256), 0, s, st.partials, S.nblk, b.c, losses);
+        hipLaunchKernelGGL(mc_loss_finish_kernel, dim3((unsigned)W), dim3(256), 0, s, st.partials, S.nbinsU, b.c, losses);
         return hipGetLastError();
     }
     const int nblk = (int)((nb + kMcEntriesPerBlock - 1) / kMcEntriesPerBlock);

@@ -37,6 +37,9 @@ def test_pack_entries_is_an_exact_copy():
     (50, 60, 64, 0.50, 2, 700),
     (40, 30, 100, 0.50, 2, 300),           # rank above a wavefront
     (64, 64, 1, 0.50, 2, 100),
+    (128, 128, 4, 0.90, 1, 300_000),       # 293 prepare workgroups of 1024 entries: more segments than one round collects
+    (128, 96, 8, 0.90, 4, 300_000),        # 2048 entries per prepare workgroup; thousands of records per bin
+    (128, 96, 8, 0.90, 8, 300_000),        # 4096 entries per prepare workgroup
 ])
 def test_mc_grad_loss_matches_oracle(m, n, r, frac, W, B, packed):
     prob = upload(wl.mc_problem(m, n, r, frac, 1.0, noise_std=0.01, seed=m + r))
