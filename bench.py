@@ -261,19 +261,19 @@ def make_mlp(cfg):
     return P, ld, x0, batches
 
 
-def run_mlp(L, steps, warmup, cfg, data):
+def run_mlp(L, steps, warmup, cfg, data, fused=True):
     dims, W, G, B, K, tau = cfg["dims"], cfg["W"], cfg["G"], cfg["B"], cfg["K"], cfg["tau"]
     P, ld, x0, host_batches = data
     x = torch.from_numpy(x0).to(DEV)
     g = torch.zeros_like(x); m = torch.zeros_like(x)
     xb = torch.zeros((W, ld), dtype=torch.bfloat16, device=DEV)
-    Z = torch.zeros((G + 1, ld), device=DEV) if tau > 1 else None
+    Z = torch.zeros((G + 1, ld), device=DEV) if (tau > 1 or fused) else None
     batches = []
     for Xb, y in host_batches:
         Xd = torch.from_numpy(Xb.view(np.int16)).to(DEV).view(torch.bfloat16)
         batches.append(L.MLPBatch(dims, Xd, torch.from_numpy(y).to(DEV)))
-    pop = L.Population(x, g, G, m=m, z_snapshot=Z, x_bf16=xb, P=P, momentum=0.9, flags=L.WRITE_BF16_SHADOW,
-                       largest_batch=batches[0])
+    pop = L.Population(x, g, G, m=m, z_snapshot=Z, x_bf16=xb, P=P, momentum=0.9,
+                       flags=L.WRITE_BF16_SHADOW | (L.FUSED_MLP_UPDATE if fused else 0), largest_batch=batches[0])
     eta, lamL, lamG = 0.01, cfg["lamL"], cfg["lamG"]
 
     def step(t):
@@ -294,16 +294,31 @@ def run_mlp(L, steps, warmup, cfg, data):
     # (forward, d-input) and write the fp32 gradient once
     wbytes = sum(dims[k] * dims[k + 1] for k in range(len(dims) - 1))
     min_bytes = float(W) * (2.0 * wbytes * 2 + 4.0 * P)
+    ms_step = secs / steps * 1e3
+    if fused:
+        # whole step with the update applied in the backward kernels: bf16 weights read by the forward and the
+        # d-input products (the first layer has no d-input), x and m read and written, bf16 copy written
+        step_bytes = float(W) * (2.0 * wbytes + 2.0 * (wbytes - dims[0] * dims[1]) + 18.0 * P)
+        gbs = step_bytes / (ms_step * 1e-3) / 1e9
+        roof = {"kernel": "lsgd_step, update applied in the backward kernels (gemm_bf16_kernel<..., EPI_DWU> dominant): all kernels of the step",
+                "bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                "bytes_per_launch": step_bytes, "ms_per_launch": ms_step,
+                "mfma_TFLOPs_of_step": flops / (ms_step * 1e-3) / 1e12}
+    else:
+        roof = {"kernel": "lsgd_grad_loss (MLP): gemm_bf16_kernel launches", "bound": "mfma", "achieved": tf,
+                "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None,
+                "flops_per_launch": flops, "ms_per_launch": ms_grad,
+                "hbm_floor_ms": min_bytes / (HBM_PEAK_GBS * 1e9) * 1e3}
     out = {
         "workload": f"{cfg['name']}, synthetic 10-class Gaussian mixture, W={W} in {G} groups, batch {B}/worker, bf16 operands / "
                     f"fp32 master, momentum 0.9, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps"
-                    + (" (staggered per group)" if cfg["staggered"] else ""),
-        "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
-        "roofline": {"kernel": "lsgd_grad_loss (MLP): gemm_bf16_kernel launches", "bound": "mfma", "achieved": tf,
-                     "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None,
-                     "flops_per_launch": flops, "ms_per_launch": ms_grad,
-                     "hbm_floor_ms": min_bytes / (HBM_PEAK_GBS * 1e9) * 1e3},
-        "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
+                    + (" (staggered per group)" if cfg["staggered"] else "")
+                    + (", update applied inside the backward kernels" if fused else ""),
+        "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": ms_step,
+        "roofline": roof,
+        "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull,
+                     "note": "separate calls (gradient through memory); the timed step " + ("fuses them" if fused else "is their sum")},
+        "grad_loss_TFLOPs": tf,
         "pull_update_GBs": W * 22.0 * P / (ms_pull * 1e-3) / 1e9,
         "final_mean_loss": float(np.mean(pop.get_losses())),
     }
@@ -336,6 +351,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-stress", action="store_true", help="skip the extra pull-update stress measurement")
+    ap.add_argument("--no-fuse", action="store_true", help="MLP workloads: three-call step instead of the fused update")
     ap.add_argument("--copy-ref", action="store_true", help="also run a plain device copy of one [W,ld] buffer (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -360,7 +376,7 @@ def main():
         cfg = MLP_CFG[args.workload]
         data = make_mlp(cfg)
         line["dtype"] = "bf16"
-        primary = run_mlp(L, args.steps, args.warmup, cfg, data)
+        primary = run_mlp(L, args.steps, args.warmup, cfg, data, fused=not args.no_fuse)
         cpu = None if args.no_cpu else cpu_mlp(cfg, data, cfg["W"] if args.workload == "c3" else 2)
     else:
         data = make_c2()
@@ -369,7 +385,7 @@ def main():
     line.update({"value": primary["value"], "unit": primary["unit"], "ms_per_step": primary["ms_per_step"],
                  "config": {"workload": primary["workload"]}, "roofline": primary["roofline"],
                  "cpu_baseline": cpu})
-    for k in ("stage_ms", "pull_update_GBs", "final_mean_loss", "ms_select", "alg1_schedule", "center"):
+    for k in ("stage_ms", "pull_update_GBs", "final_mean_loss", "ms_select", "alg1_schedule", "center", "grad_loss_TFLOPs"):
         if k in primary:
             line[k] = primary[k]
     if stress is not None:

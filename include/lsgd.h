@@ -56,7 +56,14 @@ enum {
                                      supplement, lemma on leader descent                          */
     LSGD_PULL_UNSCALED_BY_ETA = 4,/* Eq. 3 as printed: pulls are not multiplied by eta            */
     LSGD_MOMENTUM_GRAD_ONLY = 8,  /* momentum buffer accumulates g only; pulls applied outside it */
-    LSGD_WRITE_BF16_SHADOW = 16   /* pull_update also writes bf16(x) to x_bf16 (MLP operands)     */
+    LSGD_WRITE_BF16_SHADOW = 16,  /* pull_update also writes bf16(x) to x_bf16 (MLP operands)     */
+    LSGD_FUSED_MLP_UPDATE = 32    /* lsgd_step on LSGD_BATCH_MLP applies the update inside the
+                                     backward kernels (the gradient never goes through memory):
+                                     g is not written and holds unspecified values afterwards,
+                                     x_bf16 is always kept current.  Same results as the
+                                     three-call sequence up to fp32 rounding.  Needs z_snapshot
+                                     when a lambda is non-zero.  Other batch kinds and the
+                                     separate calls are unaffected.                              */
 };
 
 #define LSGD_MAX_WORKERS 32768

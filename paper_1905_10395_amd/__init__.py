@@ -6,6 +6,6 @@ and the stream.  There is no CPU fallback: importing `binding` without the
 built library raises.
 """
 from .binding import (  # noqa: F401
-    COMM_GLOBAL, COMM_LOCAL, LEADER_EXEMPT, MOMENTUM_GRAD_ONLY, NESTEROV, PULL_UNSCALED_BY_ETA, WRITE_BF16_SHADOW,
+    COMM_GLOBAL, COMM_LOCAL, FUSED_MLP_UPDATE, LEADER_EXEMPT, MOMENTUM_GRAD_ONLY, NESTEROV, PULL_UNSCALED_BY_ETA, WRITE_BF16_SHADOW,
     ExternalBatch, LsgdError, MCBatch, MLPBatch, Population, lib, lib_path, mc_pack_entries, workspace_bytes,
 )

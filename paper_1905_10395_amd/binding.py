@@ -15,6 +15,7 @@ LEADER_EXEMPT = 2
 PULL_UNSCALED_BY_ETA = 4
 MOMENTUM_GRAD_ONLY = 8
 WRITE_BF16_SHADOW = 16
+FUSED_MLP_UPDATE = 32
 COMM_LOCAL = 1
 COMM_GLOBAL = 2
 

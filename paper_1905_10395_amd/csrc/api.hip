@@ -1,6 +1,7 @@
 // Host side of the C boundary declared in lsgd.h: argument validation, the
 // population object, workspace carving and kernel dispatch.  No arithmetic of
 // the method lives here.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -61,7 +62,8 @@ lsgd_status check_config(const lsgd_config* cfg, std::vector<int32_t>* offsets_o
         return fail(LSGD_ERR_SHAPE, "n_groups=%d outside [1,min(W,%d)]", cfg->n_groups, LSGD_MAX_GROUPS);
     if (!std::isfinite(cfg->momentum) || cfg->momentum < 0.0f) return fail(LSGD_ERR_INVALID_ARG, "momentum must be finite and >= 0");
     if (!std::isfinite(cfg->weight_decay)) return fail(LSGD_ERR_INVALID_ARG, "weight_decay must be finite");
-    const int known = LSGD_NESTEROV | LSGD_LEADER_EXEMPT | LSGD_PULL_UNSCALED_BY_ETA | LSGD_MOMENTUM_GRAD_ONLY | LSGD_WRITE_BF16_SHADOW;
+    const int known = LSGD_NESTEROV | LSGD_LEADER_EXEMPT | LSGD_PULL_UNSCALED_BY_ETA | LSGD_MOMENTUM_GRAD_ONLY | LSGD_WRITE_BF16_SHADOW |
+                      LSGD_FUSED_MLP_UPDATE;
     if (cfg->flags & ~known) return fail(LSGD_ERR_INVALID_ARG, "unknown flag bits 0x%x", cfg->flags & ~known);
     std::vector<int32_t> off((size_t)cfg->n_groups + 1);
     if (cfg->group_offsets) {
@@ -390,6 +392,47 @@ lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG)
     return do_pull(p, eta, lamL, lamG, (p->cfg.flags & LSGD_PULL_UNSCALED_BY_ETA) != 0, false);
 }
 
+// forward + losses -> leaders -> kept copies brought up to date -> backward pass that applies the update
+lsgd_status do_fused_mlp_step(lsgd_population* p, const lsgd_batch* batch, float eta, float lamL, float lamG,
+                              const uint8_t* refresh_local, int refresh_global)
+{
+    const auto* d = static_cast<const lsgd_mlp_batch*>(batch->desc);
+    if ((lamL != 0.0f || lamG != 0.0f) && !p->Z) return fail(LSGD_ERR_STATE, "the fused MLP update reads leaders from z_snapshot, which is NULL");
+    hipError_t e = hipSuccess;
+    if (!p->shadow_valid) {
+        e = launch_cast_shadow(p->x, p->xb, p->cfg.W, p->cfg.P, p->cfg.ld, p->stream);
+        if (e != hipSuccess) return fail(LSGD_ERR_HIP, "cast_shadow: %s", hipGetErrorString(e));
+        p->shadow_valid = true;
+    }
+    e = launch_mlp_forward(p->xb, p->x, p->st.losses, p->cfg.W, p->cfg.P, p->cfg.ld, *d, p->st, p->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "mlp forward: %s", hipGetErrorString(e));
+    lsgd_status st = do_select(p, nullptr, refresh_local, refresh_global);
+    if (st != LSGD_OK) return st;
+    if (any_pending(p)) {
+        if (lamL != 0.0f || lamG != 0.0f) {
+            st = do_pull(p, 0.0f, 0.0f, 0.0f, false, true);            // capture only: nobody moves
+            if (st != LSGD_OK) return st;
+        } else {
+            std::fill(p->pending_local.begin(), p->pending_local.end(), (uint8_t)0);
+            p->pending_global = false;
+        }
+    }
+    FusedUpdate fu{};
+    fu.enabled = 1;
+    fu.x = p->x; fu.m = (p->cfg.momentum != 0.0f) ? p->m : nullptr; fu.xb = p->xb; fu.Z = p->Z;
+    fu.lead = p->st.lead; fu.glead = p->st.glead; fu.group_of = p->st.group_of; fu.G = p->cfg.n_groups;
+    fu.eta = eta; fu.mu = p->cfg.momentum; fu.wd = p->cfg.weight_decay; fu.flags = p->cfg.flags;
+    fu.lamL = lamL; fu.lamG = lamG;
+    if (p->cfg.flags & LSGD_PULL_UNSCALED_BY_ETA) {
+        if (lamL != 0.0f) fu.lamL = lamL / eta;
+        if (lamG != 0.0f) fu.lamG = lamG / eta;
+    }
+    e = launch_mlp_backward(p->xb, p->x, p->g, p->cfg.W, p->cfg.P, p->cfg.ld, *d, p->st, &fu, p->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "mlp backward: %s", hipGetErrorString(e));
+    p->shadow_valid = true;
+    return LSGD_OK;
+}
+
 } // namespace
 
 extern "C" {
@@ -428,6 +471,8 @@ lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, 
     if (st != LSGD_OK) return st;
     st = check_pull_state(pop, eta, lambda_L, lambda_G, refresh_local, refresh_local == nullptr, refresh_global != 0);
     if (st != LSGD_OK) return st;
+    if ((pop->cfg.flags & LSGD_FUSED_MLP_UPDATE) && batch->kind == LSGD_BATCH_MLP)
+        return do_fused_mlp_step(pop, batch, eta, lambda_L, lambda_G, refresh_local, refresh_global);
     st = do_grad_loss(pop, batch, nullptr);
     if (st != LSGD_OK) return st;
     st = do_select(pop, nullptr, refresh_local, refresh_global);

@@ -64,11 +64,34 @@ hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, i
 
 hipError_t launch_mc_pack(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n, lsgd_mc_entry* out, hipStream_t s);
 
+// When `enabled`, the kernels that produce gradient values apply the update to x (and m, and the
+// bf16 copy) themselves instead of writing g.  Leader parameters are always read from the kept
+// copies Z, which the caller has brought up to date beforehand.
+struct FusedUpdate {
+    int enabled;
+    float* x;
+    float* m;               // NULL when mu == 0
+    uint16_t* xb;
+    const float* Z;         // [(G+1)][ld]; may be NULL when both coefficients are 0
+    const int32_t* lead;
+    const int32_t* glead;
+    const int32_t* group_of;
+    int G;
+    float eta, lamL, lamG, mu, wd;   // lamL, lamG as the kernel applies them (already divided by eta if unscaled)
+    int flags;
+};
+
 size_t mlp_scratch_bytes(int W, const lsgd_mlp_batch& b);
 // returns LSGD_OK / LSGD_ERR_UNSUPPORTED through *status for shapes the kernels do not cover
 hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, float* losses, int W,
                                 int64_t P, int64_t ld, const lsgd_mlp_batch& b, const DeviceState& st,
                                 hipStream_t s);
+// the two halves of launch_mlp_grad_loss: forward pass + losses (+ output delta), then the backward pass,
+// which writes g, or applies the update when fu->enabled
+hipError_t launch_mlp_forward(const uint16_t* xb, const float* x, float* losses, int W, int64_t P, int64_t ld,
+                              const lsgd_mlp_batch& b, const DeviceState& st, hipStream_t s);
+hipError_t launch_mlp_backward(const uint16_t* xb, const float* x, float* g, int W, int64_t P, int64_t ld,
+                               const lsgd_mlp_batch& b, const DeviceState& st, const FusedUpdate* fu, hipStream_t s);
 bool mlp_shape_supported(const lsgd_mlp_batch& b, const char** why);
 
 // ---- small device helpers ----

@@ -25,6 +25,7 @@
 // register micro-transpose per thread).  delta_k is stored in both layouts by
 // the kernel that produces it.
 #include "common.h"
+#include "update_math.h"
 
 namespace lsgd {
 
@@ -32,8 +33,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-enum { EPI_FWD = 0, EPI_DX = 1, EPI_DW = 2 };
+enum { EPI_FWD = 0, EPI_DX = 1, EPI_DW = 2, EPI_DWU = 3 };   // DWU: d-weight with the update applied in place of the store
 
 struct GemmArgs {
     const uint16_t* A; int64_t sA; int64_t lda;   // [M][K], per-worker stride sA (elements)
@@ -44,7 +46,109 @@ struct GemmArgs {
     uint16_t* out; int64_t sOut; int64_t ldout;   // EPI_FWD: h [M][N]; EPI_DX: delta [M][N]
     uint16_t* outT; int64_t sOutT; int64_t ldoutT;// EPI_DX: delta^T [N][M]
     float* C; int64_t sC; int64_t ldc;            // EPI_DW: fp32 [M][N]
+    FusedUpdate fu; int64_t colC;                 // EPI_DWU: update state; column of C[0][0] in the parameter row
 };
+
+// Per-worker view of the fused update: coefficients (with the leader exemption resolved) and row pointers.
+struct FusedRow {
+    Coef c;
+    float* x;
+    float* m;
+    uint16_t* xb;
+    const float* zl;
+    const float* zg;
+};
+
+__device__ __forceinline__ FusedRow fused_row(const FusedUpdate& u, int w, int64_t ld)
+{
+    FusedRow r;
+    r.c.eta = u.eta; r.c.mu = u.mu; r.c.wd = u.wd; r.c.cL = u.lamL; r.c.cG = u.lamG;
+    r.c.nesterov = (u.flags & LSGD_NESTEROV) != 0;
+    r.c.grad_only = (u.flags & LSGD_MOMENTUM_GRAD_ONLY) != 0;
+    const int j = u.group_of[w];
+    if (u.flags & LSGD_LEADER_EXEMPT) {
+        if (u.lamL != 0.0f && u.lead[j] == w) r.c.cL = 0.0f;
+        if (u.lamG != 0.0f && u.glead[0] == w) r.c.cG = 0.0f;
+    }
+    r.x = u.x + (int64_t)w * ld;
+    r.m = u.m ? u.m + (int64_t)w * ld : nullptr;
+    r.xb = u.xb + (int64_t)w * ld;
+    r.zl = (u.lamL != 0.0f) ? u.Z + (int64_t)j * ld : nullptr;
+    r.zg = (u.lamG != 0.0f) ? u.Z + (int64_t)u.G * ld : nullptr;
+    return r;
+}
+
+// N parameters at columns base + off[0..N) of the worker's row, gradient values gv: all loads first,
+// then the arithmetic, then the stores (x, m, bf16 copy).
+template <int N>
+__device__ __forceinline__ void fused_apply(const FusedRow& r, int64_t base, const int (&off)[N], const float (&gv)[N])
+{
+    float* xp = r.x + base;
+    float* mp = r.m ? r.m + base : nullptr;
+    const float* lp = r.zl ? r.zl + base : nullptr;
+    const float* gp = r.zg ? r.zg + base : nullptr;
+    uint16_t* bp = r.xb + base;
+    float xv[N], mv[N], zl[N], zg[N];
+#pragma unroll
+    for (int v = 0; v < N; ++v) xv[v] = xp[off[v]];
+#pragma unroll
+    for (int v = 0; v < N; ++v) mv[v] = mp ? mp[off[v]] : 0.f;
+#pragma unroll
+    for (int v = 0; v < N; ++v) zl[v] = lp ? lp[off[v]] : 0.f;
+#pragma unroll
+    for (int v = 0; v < N; ++v) zg[v] = gp ? gp[off[v]] : 0.f;
+#pragma unroll
+    for (int v = 0; v < N; ++v) {
+        if (mp) update_vec<1, float>(xv[v], gv[v], mv[v], zl[v], zg[v], r.c);
+        else update_vec<0, float>(xv[v], gv[v], mv[v], zl[v], zg[v], r.c);
+    }
+#pragma unroll
+    for (int v = 0; v < N; ++v) {
+        xp[off[v]] = xv[v];
+        if (mp) mp[off[v]] = mv[v];
+        bp[off[v]] = f32_to_bf16_rne(xv[v]);
+    }
+}
+
+// R groups of four adjacent parameters (columns multiples of 4, rows 16-byte aligned): the loads of one
+// batch are issued as a block, so that they are in flight while the previous batch is updated and stored.
+template <int R>
+struct FusedBatch {
+    int64_t col[R];
+    f32x4 xv[R], mv[R], zl[R], zg[R];
+};
+
+template <int R>
+__device__ __forceinline__ void fused_load4(const FusedRow& r, FusedBatch<R>& b)
+{
+    const f32x4 zero = (f32x4)(0.f);
+#pragma unroll
+    for (int q = 0; q < R; ++q) b.xv[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r.x + b.col[q]));
+#pragma unroll
+    for (int q = 0; q < R; ++q) b.mv[q] = r.m ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r.m + b.col[q])) : zero;
+#pragma unroll
+    for (int q = 0; q < R; ++q) b.zl[q] = r.zl ? *reinterpret_cast<const f32x4*>(r.zl + b.col[q]) : zero;
+#pragma unroll
+    for (int q = 0; q < R; ++q) b.zg[q] = r.zg ? *reinterpret_cast<const f32x4*>(r.zg + b.col[q]) : zero;
+}
+
+template <int R>
+__device__ __forceinline__ void fused_store4(const FusedRow& r, FusedBatch<R>& b, const f32x4 (&gv)[R])
+{
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+        if (r.m) update_vec<1, f32x4>(b.xv[q], gv[q], b.mv[q], b.zl[q], b.zg[q], r.c);
+        else update_vec<0, f32x4>(b.xv[q], gv[q], b.mv[q], b.zl[q], b.zg[q], r.c);
+    }
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+        __builtin_nontemporal_store(b.xv[q], reinterpret_cast<f32x4*>(r.x + b.col[q]));
+        if (r.m) __builtin_nontemporal_store(b.mv[q], reinterpret_cast<f32x4*>(r.m + b.col[q]));
+        u32x2 o = {(uint32_t)f32_to_bf16_rne(b.xv[q].x) | ((uint32_t)f32_to_bf16_rne(b.xv[q].y) << 16),
+                   (uint32_t)f32_to_bf16_rne(b.xv[q].z) | ((uint32_t)f32_to_bf16_rne(b.xv[q].w) << 16)};
+        *reinterpret_cast<u32x2*>(r.xb + b.col[q]) = o;
+    }
+}
 
 constexpr int kBK = 64;          // contraction tile
 constexpr int kLdk = kBK + 8;    // padded LDS row (bf16 elements): 144 B
@@ -96,8 +200,30 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
 
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int wm = wid / WVN, wn = wid % WVN;
-    const int w = blockIdx.z;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    // Fused update: a die (workgroup id modulo 8) owns every eighth tile column, and visits its tiles
+    // row by row with the workers varying fastest.  All workers' workgroups for one tile then run
+    // together on one die, so the tile of the leader copies they share is fetched into that die's L2
+    // once; a worker's delta^T tile is reused across the die's columns and its h tiles across rows.
+    int w, tm, tn;
+    if (EPI == EPI_DWU) {
+        const int W = (int)gridDim.z, tiles_n = (int)gridDim.x;
+        const int64_t id = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        if (tiles_n % 8 == 0) {
+            const int xcd = (int)(id & 7);
+            int64_t s = id >> 3;
+            w = (int)(s % W); s /= W;
+            const int per = tiles_n / 8;
+            tn = (int)(s % per) * 8 + xcd;
+            tm = (int)(s / per);
+        } else {
+            w = (int)(id % W);
+            const int64_t tile = id / W;
+            tn = (int)(tile % tiles_n); tm = (int)(tile / tiles_n);
+        }
+    } else {
+        w = blockIdx.z; tm = blockIdx.y; tn = blockIdx.x;
+    }
+    const int m0 = tm * BM, n0 = tn * BN;
     const uint16_t* A = g.A + (int64_t)w * g.sA + (int64_t)m0 * g.lda;
     const uint16_t* B = g.B + (int64_t)w * g.sB;
 
@@ -233,6 +359,63 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
     }
 
     // epilogue: lane holds column n = lane%32 and rows (lane/32)*4 + 8*(v/4) + v%4 of each 32x32 tile
+    if (EPI == EPI_DWU) {
+        // The update streams x, m and the leader copies, so it wants whole rows per wavefront: the
+        // accumulators go through LDS (reusing the operand buffers), 32 rows of every wavefront row at a
+        // time, and come back as float4 per thread with a wavefront covering contiguous row segments.
+        constexpr int LDC = BN + 4;                       // padded fp32 row
+        constexpr int CH_ROWS = WVM * 32;                 // rows staged per round
+        constexpr int C4 = BN / 4;                        // float4 per row
+        constexpr int RPP = kGemmThreads / C4;            // rows covered by one pass of all threads
+        constexpr int PASSES = CH_ROWS / RPP;
+        constexpr int R = PASSES < 4 ? PASSES : 4;        // rows in flight per thread
+        static_assert(CH_ROWS % RPP == 0 && PASSES % R == 0, "tile shape");
+        float* stage = reinterpret_cast<float*>(smem);
+        const FusedRow fr = fused_row(g.fu, w, g.sC);
+        const int c4 = tid % C4, r0 = tid / C4;
+        constexpr int BPR = PASSES / R;                   // batches per staged round
+        constexpr int NB = TM * BPR;
+        FusedBatch<R> fb[2];
+        auto set_cols = [&](int bi, FusedBatch<R>& b) {   // batch bi = (round, pass group)
+            const int i = bi / BPR, p0 = (bi % BPR) * R;
+#pragma unroll
+            for (int q = 0; q < R; ++q) {
+                const int rr = r0 + (p0 + q) * RPP;        // row inside the staged round
+                const int m = m0 + (rr >> 5) * WTM + i * 32 + (rr & 31);
+                b.col[q] = g.colC + (int64_t)m * g.ldc + n0 + c4 * 4;
+            }
+        };
+        set_cols(0, fb[0]);
+        fused_load4<R>(fr, fb[0]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            __syncthreads();                              // operand buffers / previous round no longer read
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rl = wm * 32 + (lane >> 5) * 4 + 8 * (v >> 2) + (v & 3);
+                    stage[rl * LDC + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][v];
+                }
+            __syncthreads();
+#pragma unroll
+            for (int qb = 0; qb < BPR; ++qb) {
+                const int bi = i * BPR + qb;
+                if (bi + 1 < NB) {                        // next batch's loads fly while this one is finished
+                    set_cols(bi + 1, fb[(bi + 1) & 1]);
+                    fused_load4<R>(fr, fb[(bi + 1) & 1]);
+                }
+                f32x4 gv[R];
+#pragma unroll
+                for (int q = 0; q < R; ++q) {
+                    const int rr = r0 + (qb * R + q) * RPP;
+                    gv[q] = *reinterpret_cast<const f32x4*>(stage + rr * LDC + c4 * 4);
+                }
+                fused_store4<R>(fr, fb[bi & 1], gv);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -303,9 +486,16 @@ static bool try_mfma(const GemmArgs& g, int W, hipStream_t s)
 {
     if (g.K % kBK || g.M % 128 || g.N % 64 || !aligned_for_mfma(g)) return false;
     if (EPI == EPI_DX && (g.ldoutT % 4 || (reinterpret_cast<uintptr_t>(g.outT) & 7u) || g.sOutT % 4)) return false;
+    if (EPI == EPI_DWU) {                                  // float4 rows of x, m, Z; 8-byte groups of the bf16 copy
+        auto a16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+        if (g.colC % 4 || g.ldc % 4 || g.sC % 4 || !a16(g.fu.x) || !a16(g.fu.m) || !a16(g.fu.Z) ||
+            (reinterpret_cast<uintptr_t>(g.fu.xb) & 7u))
+            return false;
+    }
     const int64_t blocks256 = (g.M % 256 == 0 && g.N % 256 == 0) ? (int64_t)(g.M / 256) * (g.N / 256) * W : 0;
     const int64_t blocks128 = (int64_t)(g.M / 128) * (g.N / 128) * W;
-    if (blocks256 >= 256) launch_gemm<256, 256, 2, 4, TRANS_B, EPI>(g, W, s);
+    // the fused update keeps two batches of x, m and leader values in registers: no room beside a 256x256 tile
+    if (blocks256 >= 256 && EPI != EPI_DWU) launch_gemm<256, 256, 2, 4, TRANS_B, EPI>(g, W, s);
     else if (g.N % 128 == 0 && blocks128 >= 256) launch_gemm<128, 128, 2, 2, TRANS_B, EPI>(g, W, s);
     else launch_gemm<128, 64, 2, 2, TRANS_B, EPI>(g, W, s);
     return true;
@@ -384,7 +574,8 @@ __global__ __launch_bounds__(256) void loss_delta_kernel(const float* __restrict
 
 // dW[o][i] = sum_b deltaT[o][b] * h[b][i].  One thread per (o, i).
 __global__ __launch_bounds__(256) void dw_valu_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, const uint16_t* __restrict__ H,
-                                                      int64_t sH, int64_t ldh, int B, int din, int dout, float* __restrict__ g, int64_t sG)
+                                                      int64_t sH, int64_t ldh, int B, int din, int dout, float* __restrict__ g, int64_t sG,
+                                                      FusedUpdate fu, int64_t col0)
 {
     const int w = blockIdx.z, o = blockIdx.y;
     const int i = blockIdx.x * 256 + threadIdx.x;
@@ -393,11 +584,18 @@ __global__ __launch_bounds__(256) void dw_valu_kernel(const uint16_t* __restrict
     const uint16_t* h = H + (int64_t)w * sH;
     float acc = 0.f;
     for (int b = 0; b < B; ++b) acc = fmaf(bf16_to_f32(dt[b]), bf16_to_f32(h[(int64_t)b * ldh + i]), acc);
-    g[(int64_t)w * sG + (int64_t)o * din + i] = acc;
+    if (fu.enabled) {
+        const int off[1] = {0};
+        const float gv[1] = {acc};
+        fused_apply<1>(fused_row(fu, w, sG), col0 + (int64_t)o * din + i, off, gv);
+    } else {
+        g[(int64_t)w * sG + (int64_t)o * din + i] = acc;
+    }
 }
 
 // db[o] = sum_b deltaT[o][b].  One wavefront per o.
-__global__ __launch_bounds__(256) void db_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, int B, int dout, float* __restrict__ g, int64_t sG)
+__global__ __launch_bounds__(256) void db_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, int B, int dout, float* __restrict__ g, int64_t sG,
+                                                 FusedUpdate fu, int64_t col0)
 {
     const int lane = threadIdx.x & 63;
     const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -408,7 +606,15 @@ __global__ __launch_bounds__(256) void db_kernel(const uint16_t* __restrict__ de
     for (int b = lane; b < B; b += 64) acc += bf16_to_f32(dt[b]);
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
-    if (lane == 0) g[(int64_t)w * sG + o] = acc;
+    if (lane == 0) {
+        if (fu.enabled) {
+            const int off[1] = {0};
+            const float gv[1] = {acc};
+            fused_apply<1>(fused_row(fu, w, sG), col0 + o, off, gv);
+        } else {
+            g[(int64_t)w * sG + o] = acc;
+        }
+    }
 }
 
 // dprev[b][i] = bf16((sum_o delta[b][o] * Wq[o][i]) * [h[b][i] > 0]), also stored transposed.  One thread per (b, i).
@@ -472,7 +678,8 @@ __global__ __launch_bounds__(256) void fwd_narrow_kernel(const uint16_t* __restr
 // dW[o][i..i+7] for one output row o and 512 columns per workgroup; the four wavefronts split the batch
 // and combine through LDS in a fixed order.  d_in % 8 == 0.
 __global__ __launch_bounds__(256) void dw_narrow_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, const uint16_t* __restrict__ H,
-                                                        int64_t sH, int64_t ldh, int B, int din, int dout, float* __restrict__ g, int64_t sG)
+                                                        int64_t sH, int64_t ldh, int B, int din, int dout, float* __restrict__ g, int64_t sG,
+                                                        FusedUpdate fu, int64_t col0)
 {
     const int w = blockIdx.z, o = blockIdx.y;
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
@@ -498,9 +705,17 @@ __global__ __launch_bounds__(256) void dw_narrow_kernel(const uint16_t* __restri
     for (int t = 0; t < 8; ++t) red[q][lane][t] = acc[t];
     __syncthreads();
     if (q == 0 && live) {
-        float* dst = g + (int64_t)w * sG + (int64_t)o * din + (int64_t)c * 8;
+        float sum[8];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) dst[t] = ((red[0][lane][t] + red[1][lane][t]) + red[2][lane][t]) + red[3][lane][t];
+        for (int t = 0; t < 8; ++t) sum[t] = ((red[0][lane][t] + red[1][lane][t]) + red[2][lane][t]) + red[3][lane][t];
+        if (fu.enabled) {
+            const int off[8] = {0, 1, 2, 3, 4, 5, 6, 7};
+            fused_apply<8>(fused_row(fu, w, sG), col0 + (int64_t)o * din + (int64_t)c * 8, off, sum);
+        } else {
+            float* dst = g + (int64_t)w * sG + (int64_t)o * din + (int64_t)c * 8;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) dst[t] = sum[t];
+        }
     }
 }
 
@@ -617,6 +832,14 @@ size_t mlp_scratch_bytes(int W, const lsgd_mlp_batch& b) { return make_plan(b, W
 hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, float* losses, int W, int64_t P,
                                 int64_t ld, const lsgd_mlp_batch& b, const DeviceState& st, hipStream_t s)
 {
+    hipError_t e = launch_mlp_forward(xb, x, losses, W, P, ld, b, st, s);
+    if (e != hipSuccess) return e;
+    return launch_mlp_backward(xb, x, g, W, P, ld, b, st, nullptr, s);
+}
+
+hipError_t launch_mlp_forward(const uint16_t* xb, const float* x, float* losses, int W, int64_t P, int64_t ld,
+                              const lsgd_mlp_batch& b, const DeviceState& st, hipStream_t s)
+{
     const MlpPlan p = make_plan(b, W);
     const int L = p.L, B = b.B;
     uint16_t* sc16 = reinterpret_cast<uint16_t*>(st.scratch);
@@ -668,34 +891,29 @@ hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, fl
     // ---- loss and output delta ----
     hipLaunchKernelGGL(loss_delta_kernel, dim3((unsigned)W), dim3(256), 0, s, logits, sW32, b.y, B, b.dims[L],
                        sc16 + p.d[L], sc16 + p.dT[L], sW16, losses);
-    // ---- backward ----
+    return hipGetLastError();
+}
+
+// Backward pass.  Per layer, from the top: delta_{k-1} first (it reads W_k, which the fused update
+// of dW_k overwrites), then dW_k and db_k.
+hipError_t launch_mlp_backward(const uint16_t* xb, const float* x, float* g, int W, int64_t P, int64_t ld,
+                               const lsgd_mlp_batch& b, const DeviceState& st, const FusedUpdate* fu_in, hipStream_t s)
+{
+    const MlpPlan p = make_plan(b, W);
+    const int L = p.L, B = b.B;
+    uint16_t* sc16 = reinterpret_cast<uint16_t*>(st.scratch);
+    const int64_t sW16 = p.per_worker / 2;     // per-worker stride in bf16 elements
+    FusedUpdate fu{};
+    if (fu_in) fu = *fu_in;
+    const bool fused = fu.enabled != 0;
+
+    int64_t woff[64];
+    { int64_t o = 0; for (int k = 1; k <= L; ++k) { woff[k] = o; o += (int64_t)b.dims[k] * b.dims[k - 1] + b.dims[k]; } }
+
     for (int k = L; k >= 1; --k) {
         const int din = b.dims[k - 1], dout = b.dims[k];
         const uint16_t* Hin = (k == 1) ? b.X : sc16 + p.h[k - 1];
         const int64_t sHin = (k == 1) ? (int64_t)B * din : sW16;
-        // dW_k
-        {
-            GemmArgs a{};
-            a.A = sc16 + p.dT[k]; a.sA = sW16; a.lda = B;
-            a.B = Hin; a.sB = sHin; a.ldb = din;
-            a.M = dout; a.N = din; a.K = B;
-            a.C = g + woff[k]; a.sC = ld; a.ldc = din;
-            auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-            const bool vec8 = din % 8 == 0 && a16(Hin) && sHin % 8 == 0;
-            if (try_mfma<true, EPI_DW>(a, W, s)) {
-            } else if (vec8 && dout <= 64) {
-                dim3 grid((unsigned)((din / 8 + 63) / 64), (unsigned)dout, (unsigned)W);
-                hipLaunchKernelGGL(dw_narrow_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
-                                   dout, g + woff[k], ld);
-            } else {
-                dim3 grid((unsigned)((din + 255) / 256), (unsigned)dout, (unsigned)W);
-                hipLaunchKernelGGL(dw_valu_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
-                                   dout, g + woff[k], ld);
-            }
-        }
-        // db_k
-        hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, sc16 + p.dT[k], sW16, B, dout,
-                           g + woff[k] + (int64_t)dout * din, ld);
         // delta_{k-1}
         if (k > 1) {
             GemmArgs a{};
@@ -718,7 +936,32 @@ hipError_t launch_mlp_grad_loss(const uint16_t* xb, const float* x, float* g, fl
                                    (int64_t)din, B, din, dout, sc16 + p.d[k - 1], sc16 + p.dT[k - 1], sW16);
             }
         }
+        // dW_k
+        {
+            GemmArgs a{};
+            a.A = sc16 + p.dT[k]; a.sA = sW16; a.lda = B;
+            a.B = Hin; a.sB = sHin; a.ldb = din;
+            a.M = dout; a.N = din; a.K = B;
+            a.C = g + woff[k]; a.sC = ld; a.ldc = din;
+            a.fu = fu; a.colC = woff[k];
+            auto a16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+            const bool vec8 = din % 8 == 0 && a16(Hin) && sHin % 8 == 0;
+            if (fused ? try_mfma<true, EPI_DWU>(a, W, s) : try_mfma<true, EPI_DW>(a, W, s)) {
+            } else if (vec8 && dout <= 64) {
+                dim3 grid((unsigned)((din / 8 + 63) / 64), (unsigned)dout, (unsigned)W);
+                hipLaunchKernelGGL(dw_narrow_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
+                                   dout, g + woff[k], ld, fu, woff[k]);
+            } else {
+                dim3 grid((unsigned)((din + 255) / 256), (unsigned)dout, (unsigned)W);
+                hipLaunchKernelGGL(dw_valu_kernel, grid, dim3(256), 0, s, sc16 + p.dT[k], sW16, Hin, sHin, (int64_t)din, B, din,
+                                   dout, g + woff[k], ld, fu, woff[k]);
+            }
+        }
+        // db_k
+        hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, sc16 + p.dT[k], sW16, B, dout,
+                           g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
     }
+    if (fused) return hipGetLastError();          // g is not written, so there is no padding to clear
     if (ld > P)
         hipLaunchKernelGGL(zero_pad_kernel, dim3((unsigned)((ld - P + 255) / 256), (unsigned)W), dim3(256), 0, s, g, P, ld);
     return hipGetLastError();

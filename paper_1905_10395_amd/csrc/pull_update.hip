@@ -21,6 +21,7 @@
 // A re-selected leader therefore costs no extra pass over memory: the
 // "broadcast" of the paper is two rows that stay in the memory-side cache.
 #include "common.h"
+#include "update_math.h"
 
 namespace lsgd {
 
@@ -53,42 +54,6 @@ __device__ __forceinline__ void st_bf16(uint16_t* p, v4f v)
     *reinterpret_cast<v4h*>(p) = o;
 }
 __device__ __forceinline__ void st_bf16(uint16_t* p, float v) { *p = f32_to_bf16_rne(v); }
-
-struct Coef {
-    float eta, cL, cG, mu, wd;
-    int nesterov, grad_only;
-};
-
-// One parameter (or four, element-wise).  Written with plain operators so that
-// the compiler forms the fused multiply-adds itself.
-// KIND 0: gradient step, 1: gradient step with momentum, 2: Algorithm 1's communication pull
-// (x <- x - cL (x - zl), then x <- x - cG (x - zg); no gradient, momentum untouched).
-template <int KIND, class V>
-__device__ __forceinline__ void update_vec(V& x, const V g, V& m, const V zl, const V zg, const Coef& c)
-{
-    constexpr bool MOM = KIND == 1;
-    if (KIND == 2) {
-        const V y = x - c.cL * (x - zl);
-        x = y - c.cG * (y - zg);
-        return;
-    }
-    V d = g + c.wd * x;
-    const V pull = c.cL * (x - zl) + c.cG * (x - zg);
-    V step;
-    if (MOM) {
-        if (c.grad_only) {
-            m = c.mu * m + d;
-            step = (c.nesterov ? d + c.mu * m : m) + pull;
-        } else {
-            d += pull;
-            m = c.mu * m + d;
-            step = c.nesterov ? d + c.mu * m : m;
-        }
-    } else {
-        step = d + pull;
-    }
-    x = x - c.eta * step;
-}
 
 __device__ __forceinline__ v4f zero_of(v4f) { return (v4f)(0.f); }
 __device__ __forceinline__ float zero_of(float) { return 0.f; }
@@ -229,7 +194,8 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
         else
             cg.cL = 0.0f;
         if (exempt) { cg.cG = 0.0f; if (ll == gl) cg.cL = 0.0f; }
-        update_row<VEC, KIND>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);
+        if (!(COMM && cg.cL == 0.0f && cg.cG == 0.0f))           // capture only: the row does not move
+            update_row<VEC, KIND>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);
     }
     if (!pullL) return;
     // re-selected local leaders, four at a time so that their loads are all in flight together
@@ -263,7 +229,8 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
                 if (a.Z) st_vec(a.Z + (int64_t)grp[u] * a.ld + col, xv[u]);
                 Coef cl = c;
                 if (exempt) { cl.cL = 0.0f; if (row[u] == gl) cl.cG = 0.0f; }
-                apply_row<VEC, KIND>(a, o, xv[u], gv[u], mv[u], xv[u], zg, cl);
+                if (!(COMM && cl.cG == 0.0f))                         // a leader's pull to itself is zero
+                    apply_row<VEC, KIND>(a, o, xv[u], gv[u], mv[u], xv[u], zg, cl);
             }
         }
     }
@@ -285,6 +252,7 @@ static void launch_range(PullDev a, bool leaders, hipStream_t s)
         PullDev part = a;
         part.col0 = a.col0 + c0 * tpc * per_block;
         const int64_t part_tiles = (tiles - c0 * tpc) < nch * tpc ? (tiles - c0 * tpc) : nch * tpc;
+        if (KIND == 2 && a.lamL == 0.0f && a.lamG == 0.0f) break;      // capture only: no row moves
         hipLaunchKernelGGL((pull_rows_kernel<VEC, KIND>), dim3((unsigned)(nch * a.W * tpc)), dim3(kPullThreads), 0, s, part,
                            part_tiles, tpc);
     }

@@ -151,3 +151,103 @@ def test_mlp_four_layer_staggered_refresh_steps():
             pr.check_state(1e-4, "step 0", tol_m=DEEP_TOL)
     np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-3)
     pr.check_state(1e-3, f"after {steps} steps", tol_m=DEEP_TOL)
+
+
+# ---------------------------------------------------------------------------
+# Update applied inside the backward kernels (LSGD_FUSED_MLP_UPDATE): same oracle sequence
+# (gradient, selection, update), the gradient never stored.
+FUSED_CASES = [
+    # dims, W, G, B, mu, flags, wd
+    ([192, 256, 10], 16, 4, 128, 0.9, 0, 0.0),                                  # 128x64 MFMA tiles + narrow layer
+    ([192, 256, 10], 16, 4, 128, 0.0, 0, 0.0),                                  # no momentum buffer
+    ([192, 256, 10], 8, 2, 128, 0.9, L.NESTEROV, 1e-4),
+    ([192, 256, 10], 8, 2, 128, 0.5, L.MOMENTUM_GRAD_ONLY | L.NESTEROV, 1e-3),
+    ([192, 256, 10], 8, 2, 128, 0.9, L.LEADER_EXEMPT, 0.0),
+    ([192, 256, 10], 8, 2, 128, 0.0, L.PULL_UNSCALED_BY_ETA, 0.0),
+    ([100, 70, 10], 6, 3, 50, 0.9, 0, 0.0),                                     # vector-ALU kernels only
+    ([512, 512, 10], 64, 8, 64, 0.9, 0, 0.0),                                   # 256x256 tiles
+    ([256, 128, 128, 10], 8, 2, 64, 0.9, 0, 0.0),                               # two hidden layers
+]
+
+
+@pytest.mark.parametrize("dims,W,G,B,mu,flags,wd", FUSED_CASES)
+def test_fused_update_steps(dims, W, G, B, mu, flags, wd):
+    P = wl.mlp_param_count(dims)
+    ld = wl.padded_ld(P)
+    x0 = wl.mlp_init(W, dims, ld=ld, seed=91, bias_std=0.05)
+    means = wl.gmm_means(dims[0], dims[-1], seed=91)
+    Xb0, y0 = wl.gmm_batch(W, B, means, 0, seed=91)
+    b0 = L.MLPBatch(dims, dev(Xb0.view(np.int16)).view(torch.bfloat16), dev(y0))
+    pr = Pair(x0, wl.equal_group_offsets(W, G), P=P, momentum=mu, flags=flags | L.FUSED_MLP_UPDATE, weight_decay=wd,
+              shadow=True, largest_batch=b0)
+    pr.g.fill_(7.0)
+    deep = len(dims) > 3
+    eta, lamL, lamG, tau = 0.01, 0.1, 0.05, 3
+    for t in range(6):
+        Xb, y = wl.gmm_batch(W, B, means, t, seed=91)
+        batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+        rl, rg = wl.refresh_masks(t, tau, G, staggered=True, tau_G=2 * tau)
+        pr.ora.grad_loss_mlp(dims, Xb, y)
+        pr.ora.select(rl, rg); pr.ora.update(eta, lamL, lamG, rl, rg)
+        pr.pop.step(batch, eta, lamL, lamG, rl, rg)
+        if not pr.check_leaders(rl, rg):
+            pr.resync_from_oracle()
+            pr.pop.sync_shadow()
+        np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=3e-4 if t == 0 else 1e-3)
+        # the momentum buffer carries the gradient's own tolerance (one switched ReLU unit per worker, see above);
+        # from the second step on the two sides start from states up to 1e-3 apart, so allow a few such units
+        pr.check_state(1e-4 if t == 0 else 1e-3, f"step {t}",
+                       tol_m=DEEP_TOL if deep else (GRAD_TOL_MAX if t == 0 else 3 * GRAD_TOL_MAX))
+        xb = pr.xb.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(xb[:, :P], wl.to_bf16_bits(pr.x.cpu().numpy()[:, :P])), f"shadow at step {t}"
+    # padding untouched, kept copies are the oracle's up to the state tolerance
+    assert np.array_equal(pr.x.cpu().numpy()[:, P:], x0[:, P:])
+    assert rel_l2_rows(pr.Z.cpu().numpy()[:, :P], pr.ora.Z[:, :P]).max() < 1e-3
+
+
+def test_fused_update_equals_three_call_sequence():
+    """Same population stepped with and without the fused flag: identical leaders, states equal up to the
+    rounding order of the update expression."""
+    dims, W, G, B = [192, 256, 10], 8, 2, 128
+    P = wl.mlp_param_count(dims)
+    ld = wl.padded_ld(P)
+    x0 = wl.mlp_init(W, dims, ld=ld, seed=5, bias_std=0.05)
+    means = wl.gmm_means(dims[0], dims[-1], seed=5)
+    Xb, y = wl.gmm_batch(W, B, means, 0, seed=5)
+    batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+    a = Pair(x0, wl.equal_group_offsets(W, G), P=P, momentum=0.9, flags=L.WRITE_BF16_SHADOW, shadow=True, largest_batch=batch)
+    b = Pair(x0, wl.equal_group_offsets(W, G), P=P, momentum=0.9, flags=L.FUSED_MLP_UPDATE, shadow=True, largest_batch=batch)
+    for t in range(3):
+        a.pop.step(batch, 0.01, 0.1, 0.05)
+        b.pop.step(batch, 0.01, 0.1, 0.05)
+        assert a.pop.get_leaders() == b.pop.get_leaders()
+        torch.cuda.synchronize()
+        assert rel_l2_rows(b.x.cpu().numpy()[:, :P], a.x.cpu().numpy()[:, :P]).max() < 1e-6
+        assert rel_l2_rows(b.m.cpu().numpy()[:, :P], a.m.cpu().numpy()[:, :P]).max() < 1e-5
+
+
+def test_fused_update_needs_snapshot_buffer():
+    dims, W, B = [64, 32, 10], 2, 16
+    P = wl.mlp_param_count(dims)
+    x0 = wl.mlp_init(W, dims, ld=wl.padded_ld(P), seed=1)
+    means = wl.gmm_means(dims[0], dims[-1], seed=1)
+    Xb, y = wl.gmm_batch(W, B, means, 0, seed=1)
+    batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+    pr = Pair(x0, np.array([0, W], dtype=np.int32), P=P, flags=L.FUSED_MLP_UPDATE, shadow=True, snapshot=False, largest_batch=batch)
+    before = pr.x.clone()
+    with pytest.raises(L.LsgdError, match="z_snapshot"):
+        pr.pop.step(batch, 0.01, 0.1, 0.0)
+    torch.cuda.synchronize()
+    assert torch.equal(before, pr.x)
+    pr.pop.step(batch, 0.01, 0.0, 0.0)                      # plain SGD needs no leader copies
+
+
+def test_fused_update_two_layer_config_full_size_one_step():
+    dims, W, G, B = [3072, 1024, 10], 16, 4, 128
+    pr, batch, Xb, y, P, _ = make(dims, W, B, seed=3, momentum=0.9, flags=L.FUSED_MLP_UPDATE, G=G, bias_std=0.0)
+    pr.ora.grad_loss_mlp(dims, Xb, y)
+    pr.ora.select(); pr.ora.update(0.01, 0.1, 0.05)
+    pr.pop.step(batch, 0.01, 0.1, 0.05)
+    assert pr.check_leaders()
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
+    pr.check_state(1e-4, "full-size fused step", tol_m=GRAD_TOL_MAX)
