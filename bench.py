@@ -27,22 +27,29 @@ import torch
 
 import workloads as wl
 
-# HBM bytes of one pull update on the 32 x 11,689,512 stress, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by
-# reference kernels of known size (profiles/pull_update_stress_32x11689512_hbm_traffic.md).  Valid only for the
-# kernel source they were taken on: reported as null once csrc/pull_update.hip differs.
-PULL_TRAFFIC = {"source_sha256_16": "8ead91ff44c23752", "bytes_per_launch": 7.668e9, "W": 32, "P": 11_689_512}
+# Bytes between the L2 caches and memory per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by
+# reference kernels of known size (profiles/*_hbm_traffic.md).  Valid only for the kernel source they were
+# taken on: reported as null once that source file differs.
+PULL_TRAFFIC = {"file": "pull_update.hip", "source_sha256_16": "fe727aabbde7ec35", "bytes_per_launch": 7.668e9,
+                "key": (32, 11_689_512)}
+MC_TRAFFIC = {"file": "mc_grad.hip", "source_sha256_16": "6f05e859b0deda31", "bytes_per_launch": 4.191e8,
+              "key": (16, 65536, 20000, 20000, 32)}
 
 
-def _pull_traffic(W, P):
+def _traffic(rec, key):
     import hashlib
-    src = os.path.join(ROOT, "paper_1905_10395_amd", "csrc", "pull_update.hip")
+    src = os.path.join(ROOT, "paper_1905_10395_amd", "csrc", rec["file"])
     try:
         cur = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
     except OSError:
         return None
-    if cur != PULL_TRAFFIC["source_sha256_16"] or (W, P) != (PULL_TRAFFIC["W"], PULL_TRAFFIC["P"]):
+    if cur != rec["source_sha256_16"] or tuple(key) != tuple(rec["key"]):
         return None
-    return PULL_TRAFFIC["bytes_per_launch"]
+    return rec["bytes_per_launch"]
+
+
+def _pull_traffic(W, P):
+    return _traffic(PULL_TRAFFIC, (W, P))
 
 
 METRIC = "worker-steps/sec and pull-update HBM GB/s (% of peak) at W workers, 1 MI355X"
@@ -201,7 +208,8 @@ def run_c2(L, steps, warmup, data):
                     f"B={B}/worker/step, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps",
         "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
         "roofline": {"kernel": "lsgd_grad_loss stage: mc_prep + mc_side + mc_loss_finish kernels", "bound": "hbm", "achieved": ach,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "traffic": _traffic(MC_TRAFFIC, (W, B, prob.m, prob.n, prob.r)),
                      "bytes_per_launch": grad_bytes, "ms_per_launch": ms_grad},
         "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
         "pull_update_GBs": W * 12.0 * prob.P / (ms_pull * 1e-3) / 1e9,

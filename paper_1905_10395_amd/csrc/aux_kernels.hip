@@ -6,8 +6,6 @@
 
 namespace lsgd {
 
-namespace {
-
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 // One thread per worker: store the new loss into ring slot t % K, then average
@@ -67,8 +65,6 @@ __global__ __launch_bounds__(kCenterThreads) void center_kernel(const float* __r
         out[col] = (float)(s[0] / (double)W);
     }
 }
-
-} // namespace
 
 hipError_t launch_smooth_losses(float* window, int K, int64_t t, const float* losses, int W, float* out, hipStream_t s)
 {
