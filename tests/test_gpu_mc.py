@@ -119,3 +119,28 @@ def test_lsgd_steps_minibatch_groups_stale_leaders():
             pr.check_state(1e-4, "step 0")
     np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-3)
     pr.check_state(1e-3, f"after {steps} steps")
+
+
+def test_full_size_matrix_completion_config_two_steps():
+    """The benchmark's configuration at full size and in its launch shape: 20000x20000, rank 32, 1 % observed,
+    16 workers in 4 groups, 65536 sampled entries per worker, packed entry records; every output compared."""
+    prob = upload(wl.mc_problem(20000, 20000, 32, 0.01, 32 ** -0.5, noise_std=0.01))
+    W, G, B = 16, 4, 65536
+    ld = wl.padded_ld(prob.P)
+    x0 = wl.mc_init(W, prob, 32 ** -0.5, ld=ld)
+    idx = wl.mc_batches(W, B, prob.n_obs, 2)
+    idx_d = dev(idx)
+    c = 0.5 * prob.n_obs / B
+    b0 = mc_batch(prob, idx_d[0], c, packed=True)
+    pr = Pair(x0, wl.equal_group_offsets(W, G), P=prob.P, largest_batch=b0)
+    for t in range(2):
+        rl, rg = wl.refresh_masks(t, 4, G)
+        pr.ora.grad_loss_mc(prob.m, prob.n, prob.r, prob.rows, prob.cols, prob.vals, idx[t], c)
+        g_ora = pr.ora.g.copy()
+        pr.ora.select(rl, rg); pr.ora.update(0.005, 0.1, 0.05, rl, rg)
+        pr.pop.step(mc_batch(prob, idx_d[t], c, packed=True), 0.005, 0.1, 0.05, rl, rg)
+        assert pr.check_leaders(rl, rg)
+        np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-5 if t == 0 else 1e-4)
+        if t == 0:
+            assert rel_l2_rows(pr.g.cpu().numpy()[:, :prob.P], g_ora[:, :prob.P]).max() < 1e-5
+        pr.check_state(1e-4, f"step {t}")
