@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void mc_loss_finish_kernel(const float* __rest
 // ------------------------------------------------------------------------------------------
 // Binned path (r % 4 == 0, 16-byte aligned rows): no global floating-point atomics, and each
 // factor row an entry touches is gathered once per side.
-// Factor rows are grouped in bins of 64 consecutive rows (U bins, then V bins).
+// Factor rows are grouped in bins of 128 consecutive rows (U bins, then V bins).
 //   1. prepare kernel (1024 threads, E = 1024..4096 entries per workgroup): fetches each entry's
 //      (a, b, M), ranks the workgroup's entries inside their U bin and V bin with LDS counters,
 //      scans the counters, and writes every entry twice into the workgroup's own region of 2E
@@ -138,7 +138,9 @@ __global__ __launch_bounds__(256) void mc_loss_finish_kernel(const float* __rest
 // ------------------------------------------------------------------------------------------
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-constexpr int kBinRows = 64;          // factor rows per bin
+constexpr int kBinRows = 128;         // factor rows per bin (64, 128 or 256)
+constexpr int kKeyShift = (kBinRows == 64) ? 26 : (kBinRows == 128) ? 25 : 24;   // record key: row in bin above, other row below
+constexpr int kKeyMask = (1 << kKeyShift) - 1;
 constexpr int kPrepThreads = 1024;    // threads per workgroup in the prepare kernel
 constexpr int kMaxBins = 8192;        // LDS histogram capacity (U bins + V bins)
 constexpr int kXcd = 8;
@@ -146,7 +148,7 @@ constexpr int kXcd = 8;
 struct McBinned {
     int32_t* segs;   // [W][nblk][nbins+1] first record of each bin inside the workgroup's region
                      // (U bins fill [0, count), V bins [count, 2 count); entry nbins = 2 count)
-    int2* rec;       // [W][nblk][2E] (row-in-bin << 26 | other factor's row, M bits)
+    int2* rec;       // [W][nblk][2E] (row-in-bin << kKeyShift | other factor's row, M bits)
     int nbinsU, nbins, nblk, E;
 };
 
@@ -227,14 +229,35 @@ __global__ __launch_bounds__(kPrepThreads) void mc_prep_kernel(
     for (int u = 0; u < EPT; ++u) {
         if (u * kPrepThreads + t < cnt_here) {
             const int mb = __float_as_int(mv[u]);
-            rec[lhist[a[u] / kBinRows] + ru[u]] = make_int2(((a[u] % kBinRows) << 26) | b[u], mb);
-            rec[lhist[S.nbinsU + b[u] / kBinRows] + rv[u]] = make_int2(((b[u] % kBinRows) << 26) | a[u], mb);
+            rec[lhist[a[u] / kBinRows] + ru[u]] = make_int2(((a[u] % kBinRows) << kKeyShift) | b[u], mb);
+            rec[lhist[S.nbinsU + b[u] / kBinRows] + rv[u]] = make_int2(((b[u] % kBinRows) << kKeyShift) | a[u], mb);
         }
     }
 }
 
+// Sum over the LPE adjacent lanes of a lane group, result in every lane of the group.  Steps inside a
+// row of 16 lanes are data-parallel-primitive adds (swap neighbours, swap pairs, mirror 8, mirror 16:
+// after the first two steps every lane of a quad holds the quad's sum, and a mirror maps each quad onto
+// a different one); wider groups finish with lane shuffles.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int LPE>
+__device__ __forceinline__ float group_sum(float v)
+{
+    if (LPE >= 2) v = dpp_add<0xB1>(v);       // quad_perm [1,0,3,2]
+    if (LPE >= 4) v = dpp_add<0x4E>(v);       // quad_perm [2,3,0,1]
+    if (LPE >= 8) v = dpp_add<0x141>(v);      // row_half_mirror
+    if (LPE >= 16) v = dpp_add<0x140>(v);     // row_mirror
+    if (LPE >= 32) v += __shfl_xor(v, 16, 64);
+    if (LPE >= 64) v += __shfl_xor(v, 32, 64);
+    return v;
+}
+
 // One workgroup per (worker, bin).  The bin's records (one segment per prepare workgroup) are
-// staged in LDS and counting-sorted by their row inside the bin (64 integer LDS counters), so that
+// staged in LDS and counting-sorted by their row inside the bin (one integer LDS counter per row), so that
 // each lane group owns whole rows: it walks the row's records, four gathers of the other factor's
 // rows in flight, forms each record's residual against its own row, accumulates in registers and
 // writes the gradient row once (scaled by 2c).  Rows without records are written as zeros.
@@ -242,7 +265,8 @@ constexpr int kSideThreads = 256;
 constexpr int kRedCap = 1024;                     // records staged per pass
 constexpr int kSegCap = kSideThreads;             // segments collected per round
 
-template <int LPE>
+// EXACT: r == 4 * LPE, every lane of a group holds part of the row.
+template <int LPE, bool EXACT>
 __global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __restrict__ x, float* __restrict__ g, int64_t ld,
                                                              int m, int n, int r, McBinned S, float two_c,
                                                              float* __restrict__ partials, int W)
@@ -252,7 +276,7 @@ __global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __re
     constexpr int PER = kRedCap / kSideThreads;                        // records per thread and pass
     int w, gbin;
     if (!xcd_map(blockIdx.x, W, S.nbins, w, gbin)) return;
-    extern __shared__ v4f tile[];                                     // the bin's own rows [64][r]
+    extern __shared__ v4f tile[];                                     // the bin's own rows [kBinRows][r]
     __shared__ int2 sorted[kRedCap];
     __shared__ int cnt[kBinRows], start[kBinRows + 1];
     __shared__ int segoff[kSegCap + 1], segbase[kSegCap], wtot[kSideThreads / 64];
@@ -273,7 +297,8 @@ __global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __re
     const int2* rec = S.rec + (int64_t)w * S.nblk * (2 * S.E);
     const int32_t* segs = S.segs + (int64_t)w * S.nblk * (S.nbins + 1) + gbin;
     const int sub = t / LPE, q0 = t % LPE;
-    const bool lane_live = q0 < r4;
+    const bool lane_live = EXACT || q0 < r4;
+    const float* obase = other + q0 * 4;                              // this lane's four columns of a gathered row
     v4f acc[RPG];
 #pragma unroll
     for (int i = 0; i < RPG; ++i) acc[i] = (v4f)(0.f);
@@ -320,23 +345,28 @@ __global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __re
                         if (segoff[mid] <= key) lo = mid; else hi = mid;
                     }
                     mine[u] = rec[segbase[lo] + (key - segoff[lo])];
-                    rank[u] = atomicAdd(&cnt[(uint32_t)mine[u].x >> 26], 1);
+                    rank[u] = atomicAdd(&cnt[(uint32_t)mine[u].x >> kKeyShift], 1);
                 }
             }
             __syncthreads();
-            if (t < 64) {                                             // exclusive scan of the 64 row counts
-                const int cc = cnt[t];
+            if (kBinRows > 64 || t < 64) {                            // exclusive scan of the row counts
+                const int cc = (t < kBinRows) ? cnt[t] : 0;
                 int in2 = cc;
 #pragma unroll
-                for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(in2, d, 64); if (t >= d) in2 += v; }
-                start[t] = in2 - cc;
-                if (t == 63) start[64] = in2;
+                for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(in2, d, 64); if (lane >= d) in2 += v; }
+                if (kBinRows > 64) {
+                    if (lane == 63) wtot[wv] = in2;
+                    __syncthreads();
+                    for (int q = 0; q < wv; ++q) in2 += wtot[q];
+                }
+                if (t < kBinRows) start[t] = in2 - cc;
+                if (t == kBinRows - 1) start[kBinRows] = in2;
             }
             __syncthreads();
 #pragma unroll
             for (int u = 0; u < PER; ++u) {
                 const int i = t + u * kSideThreads;
-                if (i < nrec) sorted[start[(uint32_t)mine[u].x >> 26] + rank[u]] = mine[u];
+                if (i < nrec) sorted[start[(uint32_t)mine[u].x >> kKeyShift] + rank[u]] = mine[u];
             }
             __syncthreads();
 #pragma unroll
@@ -344,34 +374,31 @@ __global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __re
                 const int row = sub + i * kSubs;
                 if (row < kBinRows) {
                     const int s0 = start[row], s1 = start[row + 1];
-                    v4f mine_row = (v4f)(0.f);
-                    if (s0 < s1 && lane_live) mine_row = tile[row * r4 + q0];
-                    for (int sidx = s0; sidx < s1; sidx += 4) {
-                        int2 rc[4];
-                        v4f ov[4];
+                    if (s0 < s1) {
+                        const v4f mine_row = lane_live ? tile[row * r4 + q0] : (v4f)(0.f);
+                        float rowsq = 0.f;
+                        for (int sidx = s0; sidx < s1; sidx += 4) {
+                            // straight-line body: slots past the row's end repeat its last record with weight zero
+                            int2 rc[4];
+                            v4f ov[4];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) rc[u] = sorted[(sidx + u < s1) ? sidx + u : sidx];
+                            for (int u = 0; u < 4; ++u) rc[u] = sorted[(sidx + u < s1) ? sidx + u : s1 - 1];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            ov[u] = (lane_live && sidx + u < s1)
-                                        ? reinterpret_cast<const v4f*>(other + (int64_t)(rc[u].x & 0x3FFFFFF) * r)[q0] : (v4f)(0.f);
-                        float d[4];
+                            for (int u = 0; u < 4; ++u)
+                                ov[u] = lane_live ? *reinterpret_cast<const v4f*>(obase + (uint64_t)(uint32_t)(rc[u].x & kKeyMask) * (uint32_t)r)
+                                                  : (v4f)(0.f);
+                            float d[4];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            d[u] = mine_row.x * ov[u].x + mine_row.y * ov[u].y + mine_row.z * ov[u].z + mine_row.w * ov[u].w;
+                            for (int u = 0; u < 4; ++u)
+                                d[u] = group_sum<LPE>(mine_row.x * ov[u].x + mine_row.y * ov[u].y + mine_row.z * ov[u].z + mine_row.w * ov[u].w);
 #pragma unroll
-                        for (int sh = 1; sh < LPE; sh <<= 1) {
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) d[u] += __shfl_xor(d[u], sh, LPE);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            if (sidx + u < s1) {
-                                const float e = d[u] - __int_as_float(rc[u].y);
+                            for (int u = 0; u < 4; ++u) {
+                                const float e = (sidx + u < s1) ? d[u] - __int_as_float(rc[u].y) : 0.f;
                                 acc[i] += e * ov[u];
-                                if (q0 == 0) sq += (double)e * (double)e;
+                                rowsq = fmaf(e, e, rowsq);
                             }
                         }
+                        if (q0 == 0) sq += (double)rowsq;
                     }
                 }
             }
@@ -428,13 +455,13 @@ static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 static int mc_bins_u(const lsgd_mc_batch& b) { return (b.m + kBinRows - 1) / kBinRows; }
 static int mc_bins(const lsgd_mc_batch& b) { return mc_bins_u(b) + (b.n + kBinRows - 1) / kBinRows; }
-// entries per prepare workgroup: as many as keeps at least ~2 workgroups per compute unit busy,
+// entries per prepare workgroup: as many as keeps at least ~4 workgroups per compute unit busy,
 // more when the segment table would otherwise outgrow its bound
 static int mc_ept(int W, const lsgd_mc_batch& b)
 {
     const int64_t nb = mc_entries(b);
     int ept = 4;
-    while (ept > 1 && (int64_t)W * ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) < 512) ept >>= 1;
+    while (ept > 1 && (int64_t)W * ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) < 1024) ept >>= 1;
     while (ept < 4 && ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) * (mc_bins(b) + 1) > ((int64_t)1 << 22))
         ept <<= 1;
     return ept;
@@ -447,7 +474,7 @@ static int mc_prep_blocks(int W, const lsgd_mc_batch& b)
 static bool mc_binned_ok(int W, const lsgd_mc_batch& b)
 {
     const int64_t nb = mc_entries(b);
-    if (!(b.r % 4 == 0 && nb > 0 && nb < ((int64_t)1 << 30) && mc_bins(b) <= kMaxBins && b.m < (1 << 26) && b.n < (1 << 26) &&
+    if (!(b.r % 4 == 0 && nb > 0 && nb < ((int64_t)1 << 30) && mc_bins(b) <= kMaxBins && b.m < (1 << kKeyShift) && b.n < (1 << kKeyShift) &&
           (size_t)kBinRows * b.r * 4 <= 64 * 1024))
         return false;
     return (int64_t)mc_prep_blocks(W, b) * (mc_bins(b) + 1) <= ((int64_t)1 << 22);
@@ -480,8 +507,12 @@ static void launch_binned(const float* x, float* g, int W, int64_t ld, const lsg
         hipLaunchKernelGGL((mc_prep_kernel<2>), pgrid, dim3(kPrepThreads), plds, s, b.rows, b.cols, b.vals, b.batch_idx, nb, S, b.entries);
     else
         hipLaunchKernelGGL((mc_prep_kernel<4>), pgrid, dim3(kPrepThreads), plds, s, b.rows, b.cols, b.vals, b.batch_idx, nb, S, b.entries);
-    hipLaunchKernelGGL((mc_side_kernel<LPE>), dim3((unsigned)((int64_t)rounds * kXcd * S.nbins)), dim3(kSideThreads),
-                       (size_t)kBinRows * b.r * 4, s, x, g, ld, b.m, b.n, b.r, S, 2.0f * b.c, partials, W);
+    if (b.r == 4 * LPE)
+        hipLaunchKernelGGL((mc_side_kernel<LPE, true>), dim3((unsigned)((int64_t)rounds * kXcd * S.nbins)), dim3(kSideThreads),
+                           (size_t)kBinRows * b.r * 4, s, x, g, ld, b.m, b.n, b.r, S, 2.0f * b.c, partials, W);
+    else
+        hipLaunchKernelGGL((mc_side_kernel<LPE, false>), dim3((unsigned)((int64_t)rounds * kXcd * S.nbins)), dim3(kSideThreads),
+                           (size_t)kBinRows * b.r * 4, s, x, g, ld, b.m, b.n, b.r, S, 2.0f * b.c, partials, W);
 }
 
 hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, int64_t P, int64_t ld,
