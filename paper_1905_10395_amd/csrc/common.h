@@ -95,13 +95,15 @@ hipError_t launch_mlp_backward(const uint16_t* xb, const float* x, float* g, int
 bool mlp_shape_supported(const lsgd_mlp_batch& b, const char** why);
 
 // ---- small device helpers ----
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float v)
+// fp32 -> bf16, round to nearest even, by the hardware conversion (two values per instruction)
+typedef __bf16 lsgd_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float lsgd_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(v);
-    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16) | ((u & 0xFFFFu) ? 0x40u : 0u);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const lsgd_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, lsgd_bf16x2));
 }
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float v) { return (uint16_t)(f32x2_to_bf16x2(v, 0.f) & 0xFFFFu); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 } // namespace lsgd

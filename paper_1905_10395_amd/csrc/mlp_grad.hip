@@ -110,11 +110,11 @@ __device__ __forceinline__ void fused_apply(const FusedRow& r, int64_t base, con
     }
 }
 
-// R groups of four adjacent parameters (columns multiples of 4, rows 16-byte aligned): the loads of one
-// batch are issued as a block, so that they are in flight while the previous batch is updated and stored.
+// R groups of four adjacent parameters (columns multiples of 4, rows 16-byte aligned) at element offsets
+// `off` of the worker's row: the loads of one batch are issued as a block, so that they are in flight while the previous batch is updated and stored.
 template <int R>
 struct FusedBatch {
-    int64_t col[R];
+    int64_t off[R];
     f32x4 xv[R], mv[R], zl[R], zg[R];
 };
 
@@ -123,13 +123,13 @@ __device__ __forceinline__ void fused_load4(const FusedRow& r, FusedBatch<R>& b)
 {
     const f32x4 zero = (f32x4)(0.f);
 #pragma unroll
-    for (int q = 0; q < R; ++q) b.xv[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r.x + b.col[q]));
+    for (int q = 0; q < R; ++q) b.xv[q] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r.x + b.off[q]));
 #pragma unroll
-    for (int q = 0; q < R; ++q) b.mv[q] = r.m ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r.m + b.col[q])) : zero;
+    for (int q = 0; q < R; ++q) b.mv[q] = r.m ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(r.m + b.off[q])) : zero;
 #pragma unroll
-    for (int q = 0; q < R; ++q) b.zl[q] = r.zl ? *reinterpret_cast<const f32x4*>(r.zl + b.col[q]) : zero;
+    for (int q = 0; q < R; ++q) b.zl[q] = r.zl ? *reinterpret_cast<const f32x4*>(r.zl + b.off[q]) : zero;
 #pragma unroll
-    for (int q = 0; q < R; ++q) b.zg[q] = r.zg ? *reinterpret_cast<const f32x4*>(r.zg + b.col[q]) : zero;
+    for (int q = 0; q < R; ++q) b.zg[q] = r.zg ? *reinterpret_cast<const f32x4*>(r.zg + b.off[q]) : zero;
 }
 
 template <int R>
@@ -142,11 +142,10 @@ __device__ __forceinline__ void fused_store4(const FusedRow& r, FusedBatch<R>& b
     }
 #pragma unroll
     for (int q = 0; q < R; ++q) {
-        __builtin_nontemporal_store(b.xv[q], reinterpret_cast<f32x4*>(r.x + b.col[q]));
-        if (r.m) __builtin_nontemporal_store(b.mv[q], reinterpret_cast<f32x4*>(r.m + b.col[q]));
-        u32x2 o = {(uint32_t)f32_to_bf16_rne(b.xv[q].x) | ((uint32_t)f32_to_bf16_rne(b.xv[q].y) << 16),
-                   (uint32_t)f32_to_bf16_rne(b.xv[q].z) | ((uint32_t)f32_to_bf16_rne(b.xv[q].w) << 16)};
-        *reinterpret_cast<u32x2*>(r.xb + b.col[q]) = o;
+        __builtin_nontemporal_store(b.xv[q], reinterpret_cast<f32x4*>(r.x + b.off[q]));
+        if (r.m) __builtin_nontemporal_store(b.mv[q], reinterpret_cast<f32x4*>(r.m + b.off[q]));
+        const u32x2 o = {f32x2_to_bf16x2(b.xv[q].x, b.xv[q].y), f32x2_to_bf16x2(b.xv[q].z, b.xv[q].w)};
+        *reinterpret_cast<u32x2*>(r.xb + b.off[q]) = o;
     }
 }
 
@@ -382,7 +381,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
             for (int q = 0; q < R; ++q) {
                 const int rr = r0 + (p0 + q) * RPP;        // row inside the staged round
                 const int m = m0 + (rr >> 5) * WTM + i * 32 + (rr & 31);
-                b.col[q] = g.colC + (int64_t)m * g.ldc + n0 + c4 * 4;
+                b.off[q] = g.colC + (int64_t)m * g.ldc + n0 + c4 * 4;
             }
         };
         set_cols(0, fb[0]);

@@ -50,8 +50,9 @@ __device__ __forceinline__ void st_stream(float* p, float v) { __builtin_nontemp
 
 __device__ __forceinline__ void st_bf16(uint16_t* p, v4f v)
 {
-    v4h o = {f32_to_bf16_rne(v.x), f32_to_bf16_rne(v.y), f32_to_bf16_rne(v.z), f32_to_bf16_rne(v.w)};
-    *reinterpret_cast<v4h*>(p) = o;
+    typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+    const v2u o = {f32x2_to_bf16x2(v.x, v.y), f32x2_to_bf16x2(v.z, v.w)};
+    *reinterpret_cast<v2u*>(p) = o;
 }
 __device__ __forceinline__ void st_bf16(uint16_t* p, float v) { *p = f32_to_bf16_rne(v); }
 
