@@ -183,7 +183,7 @@ template <int BN, int THREADS> __device__ __forceinline__ void trans_map(int tid
 // 128x128 / 128x64 with 2x2 wavefronts run two workgroups per CU; 256x256 with 2x4 wavefronts
 // (128x64 per wavefront, all 147 KB of LDS) moves half the bytes through LDS per flop.
 template <int BM, int BN, int WVM, int WVN, bool TRANS_B, int EPI>
-__global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_bf16_kernel(GemmArgs g)
+__global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_bf16_kernel(GemmArgs g)  // min. workgroups per CU
 {
     constexpr int kGemmThreads = 64 * WVM * WVN;
     constexpr int WTM = BM / WVM, WTN = BN / WVN;
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
     constexpr int A_CHUNKS = BM * (kBK / 8) / kGemmThreads; // 16-byte chunks per thread
     constexpr int B_CHUNKS = BN * (kBK / 8) / kGemmThreads;
     constexpr int KK = kBK * BN / 8 / kGemmThreads;  // k-rows per thread in the transposing stage
-    constexpr int STAGES = (WVM * WVN > 4) ? 1 : 2;  // register stages of global prefetch
+    constexpr int STAGES = (TM * TN > 4) ? 1 : 2;    // register stages of global prefetch (one beside 128 accumulator registers)
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t* As = smem;                              // [2][BM][kLdk]
@@ -494,7 +494,10 @@ static bool try_mfma(const GemmArgs& g, int W, hipStream_t s)
     const int64_t blocks256 = (g.M % 256 == 0 && g.N % 256 == 0) ? (int64_t)(g.M / 256) * (g.N / 256) * W : 0;
     const int64_t blocks128 = (int64_t)(g.M / 128) * (g.N / 128) * W;
     // the fused update keeps two batches of x, m and leader values in registers: no room beside a 256x256 tile
+    // a 256-row tile covers a whole batch of 256: the weight operand is then read once instead of twice
+    const int64_t blocks_tall = (g.M % 256 == 0 && g.N % 128 == 0) ? (int64_t)(g.M / 256) * (g.N / 128) * W : 0;
     if (blocks256 >= 256 && EPI != EPI_DWU) launch_gemm<256, 256, 2, 4, TRANS_B, EPI>(g, W, s);
+    else if ((EPI == EPI_FWD || EPI == EPI_DX) && blocks_tall >= 256) launch_gemm<256, 128, 4, 2, TRANS_B, EPI>(g, W, s);
     else if (g.N % 128 == 0 && blocks128 >= 256) launch_gemm<128, 128, 2, 2, TRANS_B, EPI>(g, W, s);
     else launch_gemm<128, 64, 2, 2, TRANS_B, EPI>(g, W, s);
     return true;

@@ -73,6 +73,8 @@ SHAPES = [
     ([512, 1024, 10], 32, 128),               # d-weight on 256x256 tiles (8 wavefronts)
     ([64, 1024, 10], 64, 256),                # forward on 256x256 tiles
     ([64, 1024, 256, 10], 64, 256),           # forward and d-input on 256x256 tiles
+    ([64, 512, 10], 64, 256),                 # forward on the 256x128 tile (whole batch per tile)
+    ([64, 512, 128, 10], 64, 256),            # d-input on the 256x128 tile
 ]
 
 
