@@ -334,21 +334,25 @@ def run_mlp(L, steps, warmup, cfg, data, fused=True):
     return out
 
 
-def cpu_mlp(cfg, data, workers):
+def cpu_mlp(cfg, data, workers, batch_frac=1.0):
+    """Oracle steps on `workers` of the W workers; with batch_frac < 1 on that share of each batch (the cost of a
+    step is proportional to the batch), scaled back to whole steps."""
     import oracle
     dims, W, G, B = cfg["dims"], cfg["W"], cfg["G"], cfg["B"]
     P, ld, x0, host_batches = data
     Ws = min(workers, W)
+    Bs = max(1, int(round(B * batch_frac)))
     pop = oracle.Population(x0[:Ws], np.array([0, Ws], dtype=np.int32), momentum=0.9, P=P)
     reps, t0 = 0, time.perf_counter()
     while reps < 1 or time.perf_counter() - t0 < 8.0:
         Xb, y = host_batches[reps % len(host_batches)]
-        pop.grad_loss_mlp(dims, np.ascontiguousarray(Xb[:Ws]), np.ascontiguousarray(y[:Ws]))
+        pop.grad_loss_mlp(dims, np.ascontiguousarray(Xb[:Ws, :Bs]), np.ascontiguousarray(y[:Ws, :Bs]))
         pop.select(); pop.update(0.01, cfg["lamL"], cfg["lamG"])
         reps += 1
     dt = (time.perf_counter() - t0) / reps
-    return {"value": Ws / dt, "unit": "worker-steps/s", "cores": _omp_threads() or os.cpu_count(), "kind": "oracle",
-            "sample": f"{Ws} of the {W} workers (one group), full batch {B} and full model, {reps} whole steps"}
+    what = f"full batch {B}" if Bs == B else f"{Bs} of the {B} samples of each batch (rate scaled by {Bs}/{B})"
+    return {"value": Ws / dt * (Bs / B), "unit": "worker-steps/s", "cores": min(Ws, _omp_threads() or os.cpu_count()), "kind": "oracle",
+            "sample": f"{Ws} of the {W} workers (one group), {what}, full model, {reps} whole steps"}
 
 
 def main():
@@ -385,7 +389,7 @@ def main():
         data = make_mlp(cfg)
         line["dtype"] = "bf16"
         primary = run_mlp(L, args.steps, args.warmup, cfg, data, fused=not args.no_fuse)
-        cpu = None if args.no_cpu else cpu_mlp(cfg, data, cfg["W"] if args.workload == "c3" else 2)
+        cpu = None if args.no_cpu else (cpu_mlp(cfg, data, cfg["W"]) if args.workload == "c3" else cpu_mlp(cfg, data, 4, 0.25))
     else:
         data = make_c2()
         primary = run_c2(L, args.steps, args.warmup, data)

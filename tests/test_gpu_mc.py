@@ -37,6 +37,10 @@ def test_pack_entries_is_an_exact_copy():
     (50, 60, 64, 0.50, 2, 700),
     (40, 30, 100, 0.50, 2, 300),           # rank above a wavefront
     (64, 64, 1, 0.50, 2, 100),
+    (70, 90, 16, 0.50, 2, 900),            # four lanes per row
+    (70, 90, 12, 0.50, 2, 900),            # four lanes per row, one of them idle
+    (40, 30, 128, 0.50, 2, 300),           # 32 lanes per row: the sum crosses 16-lane rows
+    (300, 10, 8, 0.50, 3, 2000),           # two lanes per row; one short side
     (128, 128, 4, 0.90, 1, 300_000),       # 293 prepare workgroups of 1024 entries: more segments than one round collects
     (128, 96, 8, 0.90, 4, 300_000),        # 2048 entries per prepare workgroup; thousands of records per bin
     (128, 96, 8, 0.90, 8, 300_000),        # 4096 entries per prepare workgroup
