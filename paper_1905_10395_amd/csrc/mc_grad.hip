@@ -224,15 +224,19 @@ __global__ __launch_bounds__(kPrepThreads) void mc_prep_kernel(
     __syncthreads();
     int32_t* seg = S.segs + ((int64_t)w * S.nblk + blk) * (S.nbins + 1);
     for (int i = t; i <= S.nbins; i += kPrepThreads) seg[i] = lhist[i];
-    int2* rec = S.rec + ((int64_t)w * S.nblk + blk) * (2 * E);
+    // the records take their sorted places in LDS first, so that they leave as one contiguous run
+    int2* stage = reinterpret_cast<int2*>(lhist + ((S.nbins + 2) & ~1));     // [2 E], 8-byte aligned behind the counters
 #pragma unroll
     for (int u = 0; u < EPT; ++u) {
         if (u * kPrepThreads + t < cnt_here) {
             const int mb = __float_as_int(mv[u]);
-            rec[lhist[a[u] / kBinRows] + ru[u]] = make_int2(((a[u] % kBinRows) << kKeyShift) | b[u], mb);
-            rec[lhist[S.nbinsU + b[u] / kBinRows] + rv[u]] = make_int2(((b[u] % kBinRows) << kKeyShift) | a[u], mb);
+            stage[lhist[a[u] / kBinRows] + ru[u]] = make_int2(((a[u] % kBinRows) << kKeyShift) | b[u], mb);
+            stage[lhist[S.nbinsU + b[u] / kBinRows] + rv[u]] = make_int2(((b[u] % kBinRows) << kKeyShift) | a[u], mb);
         }
     }
+    __syncthreads();
+    int2* rec = S.rec + ((int64_t)w * S.nblk + blk) * (2 * E);
+    for (int i = t; i < 2 * cnt_here; i += kPrepThreads) rec[i] = stage[i];
 }
 
 // Sum over the LPE adjacent lanes of a lane group, result in every lane of the group.  Steps inside a
@@ -500,7 +504,13 @@ static void launch_binned(const float* x, float* g, int W, int64_t ld, const lsg
 {
     const int rounds = (W + kXcd - 1) / kXcd;
     const dim3 pgrid((unsigned)S.nblk, (unsigned)W);
-    const size_t plds = (size_t)(S.nbins + 1) * 4;
+    const size_t plds = (size_t)((S.nbins + 2) & ~1) * 4 + (size_t)2 * S.E * 8;     // counters, then the staged records
+    static bool big_lds = false;
+    if (!big_lds) {                                   // 4096 entries per workgroup stage 64 KB of records
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&mc_prep_kernel<4>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)((kMaxBins + 2) * 4 + 2 * 4 * kPrepThreads * 8));
+        big_lds = true;
+    }
     if (S.E == kPrepThreads)
         hipLaunchKernelGGL((mc_prep_kernel<1>), pgrid, dim3(kPrepThreads), plds, s, b.rows, b.cols, b.vals, b.batch_idx, nb, S, b.entries);
     else if (S.E == 2 * kPrepThreads)
