@@ -459,13 +459,13 @@ static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 
 static int mc_bins_u(const lsgd_mc_batch& b) { return (b.m + kBinRows - 1) / kBinRows; }
 static int mc_bins(const lsgd_mc_batch& b) { return mc_bins_u(b) + (b.n + kBinRows - 1) / kBinRows; }
-// entries per prepare workgroup: as many as keeps at least ~4 workgroups per compute unit busy,
+// entries per prepare workgroup: as many as keeps at least ~2 workgroups per compute unit busy,
 // more when the segment table would otherwise outgrow its bound
 static int mc_ept(int W, const lsgd_mc_batch& b)
 {
     const int64_t nb = mc_entries(b);
     int ept = 4;
-    while (ept > 1 && (int64_t)W * ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) < 1024) ept >>= 1;
+    while (ept > 1 && (int64_t)W * ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) < 512) ept >>= 1;
     while (ept < 4 && ((nb + (int64_t)ept * kPrepThreads - 1) / ((int64_t)ept * kPrepThreads)) * (mc_bins(b) + 1) > ((int64_t)1 << 22))
         ept <<= 1;
     return ept;

@@ -332,15 +332,19 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
         store_lds(0, ra0, rb0);
         if (nk > 2) load_global(2, ra0, rb0);
         __syncthreads();
-        for (int kt = 0; kt < nk; kt += 2) {
-            if (kt + 1 < nk) store_lds(1, ra1, rb1);
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {                    // both halves always run: no exit in the middle of the body
+            store_lds(1, ra1, rb1);
             if (kt + 3 < nk) load_global(kt + 3, ra1, rb1);
             compute(0);
             __syncthreads();
-            if (kt + 1 >= nk) break;
             if (kt + 2 < nk) store_lds(0, ra0, rb0);
             if (kt + 4 < nk) load_global(kt + 4, ra0, rb0);
             compute(1);
+            __syncthreads();
+        }
+        if (kt < nk) {                                    // odd number of k-steps: the last one sits in buffer 0
+            compute(0);
             __syncthreads();
         }
     } else {
