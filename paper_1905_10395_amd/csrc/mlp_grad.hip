@@ -698,7 +698,21 @@ __global__ __launch_bounds__(256) void dw_narrow_kernel(const uint16_t* __restri
     for (int t = 0; t < 8; ++t) acc[t] = 0.f;
     const int b0 = (int)((int64_t)B * q / 4), b1 = (int)((int64_t)B * (q + 1) / 4);
     if (live) {
-        for (int b = b0; b < b1; ++b) {
+        int b = b0;
+        for (; b + 8 <= b1; b += 8) {                     // eight rows of h in flight
+            u32x4 hv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) hv[u] = *reinterpret_cast<const u32x4*>(h + (int64_t)(b + u) * ldh + (int64_t)c * 8);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float d = bf16_to_f32(dt[b + u]);
+                float a[8];
+                unpack8(hv[u], a);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) acc[t] = fmaf(d, a[t], acc[t]);
+            }
+        }
+        for (; b < b1; ++b) {
             const float d = bf16_to_f32(dt[b]);
             float a[8];
             unpack8(*reinterpret_cast<const u32x4*>(h + (int64_t)b * ldh + (int64_t)c * 8), a);
