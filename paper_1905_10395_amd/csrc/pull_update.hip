@@ -120,19 +120,11 @@ __device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename
 // of the die that reads them instead of being fetched again for each row.
 constexpr int kChunkTiles = 1024;
 
+// VEC adjacent columns of one row, starting at col.
 template <int VEC, int KIND>
-__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int64_t tiles, int tpc)
+__device__ __forceinline__ void pull_rows_body(const PullDev& a, int row, int64_t col)
 {
     using V = typename Vec<VEC>::type;
-    const int64_t b = blockIdx.x;
-    const int64_t per_chunk = (int64_t)a.W * tpc;
-    const int64_t chunk = b / per_chunk;
-    const int rem = (int)(b - chunk * per_chunk);
-    const int row = rem / tpc;
-    const int64_t tile = chunk * tpc + (rem - row * tpc);
-    if (tile >= tiles) return;
-    const int64_t col = a.col0 + (tile * kPullThreads + threadIdx.x) * VEC;
-    if (col >= a.col1) return;
     constexpr bool COMM = KIND == 2;       // communication pull: every re-selected leader is captured
     bool pullG = COMM || a.lamG != 0.0f, pullL = COMM || a.lamL != 0.0f;
     const int j = a.group_size ? row / a.group_size : a.group_of[row];
@@ -161,6 +153,26 @@ __global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int6
     update_row<VEC, KIND>(a, o, xv, zl, zg, c);
 }
 
+// A thread of the 4-wide kernel whose group straddles the end of the row takes its columns one by one.
+template <int VEC, int KIND>
+__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int64_t tiles, int tpc)
+{
+    const int64_t b = blockIdx.x;
+    const int64_t per_chunk = (int64_t)a.W * tpc;
+    const int64_t chunk = b / per_chunk;
+    const int rem = (int)(b - chunk * per_chunk);
+    const int row = rem / tpc;
+    const int64_t tile = chunk * tpc + (rem - row * tpc);
+    if (tile >= tiles) return;
+    const int64_t col = a.col0 + (tile * kPullThreads + threadIdx.x) * VEC;
+    if (col >= a.col1) return;
+    if (VEC == 1 || col + VEC <= a.col1) {
+        pull_rows_body<VEC, KIND>(a, row, col);
+    } else {
+        for (int64_t cc = col; cc < a.col1; ++cc) pull_rows_body<1, KIND>(a, row, cc);
+    }
+}
+
 // Kernel 2 (runs after kernel 1): the rows that were captured as leaders.  A
 // workgroup owns a column tile for all of them, so it can take every copy it
 // needs before it stores anything: first the global leader's tile, whose own
@@ -168,11 +180,9 @@ __global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int6
 // untouched), then each re-selected local leader, whose pull to itself is
 // exactly zero.  Captured tiles are also written to the kept-copy buffer Z.
 template <int VEC, int KIND>
-__global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
+__device__ __forceinline__ void pull_leaders_body(const PullDev& a, int64_t col)
 {
     using V = typename Vec<VEC>::type;
-    const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
-    if (col >= a.col1) return;
     constexpr bool COMM = KIND == 2;
     const bool pullG = COMM ? a.refreshed[a.G] != 0 : a.lamG != 0.0f, pullL = COMM || a.lamL != 0.0f;
     const bool exempt = !COMM && (a.flags & LSGD_LEADER_EXEMPT) != 0;
@@ -238,6 +248,18 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
 }
 
 template <int VEC, int KIND>
+__global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
+{
+    const int64_t col = a.col0 + ((int64_t)blockIdx.x * kPullThreads + threadIdx.x) * VEC;
+    if (col >= a.col1) return;
+    if (VEC == 1 || col + VEC <= a.col1) {
+        pull_leaders_body<VEC, KIND>(a, col);
+    } else {
+        for (int64_t cc = col; cc < a.col1; ++cc) pull_leaders_body<1, KIND>(a, cc);
+    }
+}
+
+template <int VEC, int KIND>
 static void launch_range(PullDev a, bool leaders, hipStream_t s)
 {
     const int64_t cols = a.col1 - a.col0;
@@ -276,13 +298,14 @@ hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStr
     auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
     const bool vec_ok = (p.ld % 4 == 0) && aligned16(p.x) && (comm || aligned16(p.g)) && (!mom || aligned16(p.m)) &&
                         (!p.Z || aligned16(p.Z)) && (!p.xb || (reinterpret_cast<uintptr_t>(p.xb) & 7u) == 0);
-    const int64_t P4 = vec_ok ? (p.P & ~(int64_t)3) : 0;
-    // whole float4 columns, then the ragged tail (or everything) element-wise;
-    // the two column ranges are disjoint, so their launches are independent
-    a.col0 = 0; a.col1 = P4;
-    if (comm) launch_range<4, 2>(a, leaders, s); else if (mom) launch_range<4, 1>(a, leaders, s); else launch_range<4, 0>(a, leaders, s);
-    a.col0 = P4; a.col1 = p.P;
-    if (comm) launch_range<1, 2>(a, leaders, s); else if (mom) launch_range<1, 1>(a, leaders, s); else launch_range<1, 0>(a, leaders, s);
+    // float4 columns when the layout allows (a ragged last group is finished element-wise by its thread),
+    // else everything element-wise
+    a.col0 = 0; a.col1 = p.P;
+    if (vec_ok) {
+        if (comm) launch_range<4, 2>(a, leaders, s); else if (mom) launch_range<4, 1>(a, leaders, s); else launch_range<4, 0>(a, leaders, s);
+    } else {
+        if (comm) launch_range<1, 2>(a, leaders, s); else if (mom) launch_range<1, 1>(a, leaders, s); else launch_range<1, 0>(a, leaders, s);
+    }
     return hipGetLastError();
 }
 
