@@ -30,9 +30,9 @@ import workloads as wl
 # Bytes between the L2 caches and memory per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by
 # reference kernels of known size (profiles/*_hbm_traffic.md).  Valid only for the kernel source they were
 # taken on: reported as null once that source file differs.
-PULL_TRAFFIC = {"file": "pull_update.hip", "source_sha256_16": "73490513434ba9f4", "bytes_per_launch": 7.668e9,
+PULL_TRAFFIC = {"file": "pull_update.hip", "source_sha256_16": "0a5c6e02208ed34b", "bytes_per_launch": 7.668e9,
                 "key": (32, 11_689_512)}
-MC_TRAFFIC = {"file": "mc_grad.hip", "source_sha256_16": "d40d248b010281b1", "bytes_per_launch": 3.953e8,
+MC_TRAFFIC = {"file": "mc_grad.hip", "source_sha256_16": "7fd40070af6d3974", "bytes_per_launch": 3.935e8,
               "key": (16, 65536, 20000, 20000, 32)}
 
 
