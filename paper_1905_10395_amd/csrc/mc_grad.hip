@@ -267,7 +267,7 @@ __device__ __forceinline__ float group_sum(float v)
 // writes the gradient row once (scaled by 2c).  Rows without records are written as zeros.
 constexpr int kSideThreads = 256;
 constexpr int kRedCap = 1024;                     // records staged per pass
-constexpr int kSegCap = kSideThreads;             // segments collected per round
+constexpr int kSegCap = kSideThreads;             // segments collected at a time
 
 // EXACT: r == 4 * LPE, every lane of a group holds part of the row.
 template <int LPE, bool EXACT>
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(kSideThreads) void mc_side_kernel(const float* __re
 
     for (int blk0 = 0; blk0 < S.nblk; blk0 += kSegCap) {
         const int nseg = (S.nblk - blk0 < kSegCap) ? S.nblk - blk0 : kSegCap;
-        // this round's segments: thread t takes segment t, counts are scanned into segoff
+        // these segments: thread t takes segment t, counts are scanned into segoff
         int c = 0;
         if (t < nseg) {
             const int blk = blk0 + t;

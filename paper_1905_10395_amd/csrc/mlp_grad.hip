@@ -367,7 +367,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
         // accumulators go through LDS (reusing the operand buffers), 32 rows of every wavefront row at a
         // time, and come back as float4 per thread with a wavefront covering contiguous row segments.
         constexpr int LDC = BN + 4;                       // padded fp32 row
-        constexpr int CH_ROWS = WVM * 32;                 // rows staged per round
+        constexpr int CH_ROWS = WVM * 32;                 // rows staged at a time
         constexpr int C4 = BN / 4;                        // float4 per row
         constexpr int RPP = kGemmThreads / C4;            // rows covered by one pass of all threads
         constexpr int PASSES = CH_ROWS / RPP;
@@ -376,14 +376,14 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
         float* stage = reinterpret_cast<float*>(smem);
         const FusedRow fr = fused_row(g.fu, w, g.sC);
         const int c4 = tid % C4, r0 = tid / C4;
-        constexpr int BPR = PASSES / R;                   // batches per staged round
+        constexpr int BPR = PASSES / R;                   // batches per staged block of rows
         constexpr int NB = TM * BPR;
         FusedBatch<R> fb[2];
-        auto set_cols = [&](int bi, FusedBatch<R>& b) {   // batch bi = (round, pass group)
+        auto set_cols = [&](int bi, FusedBatch<R>& b) {   // batch bi = (staged block, pass group)
             const int i = bi / BPR, p0 = (bi % BPR) * R;
 #pragma unroll
             for (int q = 0; q < R; ++q) {
-                const int rr = r0 + (p0 + q) * RPP;        // row inside the staged round
+                const int rr = r0 + (p0 + q) * RPP;        // row inside the staged block
                 const int m = m0 + (rr >> 5) * WTM + i * 32 + (rr & 31);
                 b.off[q] = g.colC + (int64_t)m * g.ldc + n0 + c4 * 4;
             }
@@ -392,7 +392,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
         fused_load4<R>(fr, fb[0]);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            __syncthreads();                              // operand buffers / previous round no longer read
+            __syncthreads();                              // operand buffers / previous block no longer read
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
