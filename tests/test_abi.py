@@ -61,3 +61,13 @@ def test_validation_happens_before_device_work():
     with pytest.raises(L.LsgdError, match=r"\(m\+n\)\*r"):
         L.workspace_bytes(4, 10, 12, 2, batch=mc)
     assert L.workspace_bytes(4, 14, 16, 2, batch=mc) > 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
