@@ -186,7 +186,11 @@ lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses,
 lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, float lambda_G);
 
 /* grad_loss -> select_leaders -> pull_update with the population's own loss
- * buffer.  The first step of a population must refresh everything.            */
+ * buffer.  The first step of a population must refresh everything.  With
+ * LSGD_FUSED_MLP_UPDATE and an LSGD_BATCH_MLP batch the same three stages run as
+ * forward pass + losses -> select_leaders -> kept copies brought up to date ->
+ * backward pass that applies the update (see the flag); the state afterwards is
+ * the same up to fp32 rounding, except that g is left unspecified.             */
 lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, float lambda_L,
                       float lambda_G, const uint8_t* refresh_local, int refresh_global);
 
