@@ -200,10 +200,15 @@ __device__ __forceinline__ void pull_leaders_body(const PullDev& a, int64_t col)
         V zl = zero_of(V());
         Coef cg = c;
         if (COMM && !a.refreshed[j]) cg.cL = 0.0f;       // its group did not communicate: no local pull
-        if (pullL && cg.cL != 0.0f)
-            zl = (ll == gl) ? zg : ld_vec<VEC>((a.refreshed[j] ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
-        else
+        // its group's leader copy: the live row only when that group re-selected too (then a row
+        // equal to gl is this very tile); a group that kept its leader pulls to the stored copy,
+        // also when the kept leader is gl itself (the copy taken at the start of the period)
+        if (pullL && cg.cL != 0.0f) {
+            const bool freshL = a.refreshed[j] != 0;
+            zl = (freshL && ll == gl) ? zg : ld_vec<VEC>((freshL ? a.x + (int64_t)ll * a.ld : a.Z + (int64_t)j * a.ld) + col);
+        } else {
             cg.cL = 0.0f;
+        }
         if (exempt) { cg.cG = 0.0f; if (ll == gl) cg.cL = 0.0f; }
         if (!(COMM && cg.cL == 0.0f && cg.cG == 0.0f))           // capture only: the row does not move
             update_row<VEC, KIND>(a, (int64_t)gl * a.ld + col, zg, zl, zg, cg);

@@ -16,6 +16,28 @@ def dev(a, dtype=None):
     return t.to(DEV)
 
 
+EPS32 = float(np.finfo(np.float32).eps)
+
+
+def assert_update_elementwise(new_gpu, new_ora, old, what="", k_self=2.0, k_row=16.0):
+    """One update from identical pre-update values `old`: every element of the GPU result must equal the
+    oracle's up to fp32 rounding of the update expression.  The oracle evaluates the expression in fp64 and
+    rounds once; the GPU chains fp32 operations whose individual roundings are relative to the terms of the
+    expression (which may cancel), so the bound per element is k_self ulps of the value itself plus k_row ulps
+    of the largest displacement in its row.  A missing pull term, a wrong leader copy or a skipped element is
+    orders of magnitude above this."""
+    new_gpu = np.asarray(new_gpu, dtype=np.float64); new_ora = np.asarray(new_ora, dtype=np.float64)
+    old = np.asarray(old, dtype=np.float64)
+    disp = np.abs(new_ora - old)
+    bound = k_self * EPS32 * np.abs(new_ora) + k_row * EPS32 * disp.max(axis=-1, keepdims=True) + 1e-37
+    err = np.abs(new_gpu - new_ora)
+    bad = err > bound
+    if bad.any():
+        i = np.unravel_index(np.argmax(err / bound), err.shape)
+        raise AssertionError(f"{what}: {int(bad.sum())} elements beyond fp32 rounding; worst at {i}: gpu {new_gpu[i]!r} "
+                             f"oracle {new_ora[i]!r} old {old[i]!r} err {err[i]:.3e} bound {bound[i]:.3e}")
+
+
 def rel_l2_rows(a, b):
     """Per-row relative L2 error of a against b (b is the oracle)."""
     a = np.asarray(a, dtype=np.float64); b = np.asarray(b, dtype=np.float64)
@@ -61,6 +83,31 @@ class Pair:
             assert self.ora.gaps[self.G] < gap_tol, (gl, self.ora.glead, self.ora.gaps)
             ok = False
         return ok
+
+    def follow_gpu(self):
+        """Make the oracle's state the GPU's (x, m, kept copies), so that the next step on both sides starts
+        from identical values and can be compared element by element; returns the pre-step (x, m)."""
+        torch.cuda.synchronize()
+        self.ora.x[:] = self.x.cpu().numpy()
+        if self.m is not None:
+            self.ora.m[:] = self.m.cpu().numpy()
+        if self.Z is not None:
+            Z = self.Z.cpu().numpy()
+            ok = ~np.isnan(Z)
+            self.ora.Z[ok] = Z[ok]
+        return self.ora.x.copy(), (None if self.m is None else self.ora.m.copy())
+
+    def check_step_elementwise(self, before, what="", k_self=2.0):
+        """After one update from the state `before` = follow_gpu(): x and m element by element."""
+        torch.cuda.synchronize()
+        P = self.P
+        x_old, m_old = before
+        assert_update_elementwise(self.x.cpu().numpy()[:, :P], self.ora.x[:, :P], x_old[:, :P], f"{what} x", k_self=k_self)
+        if self.m is not None:
+            # m+ = mu m + d: the displacement scale of m is |m+| itself
+            assert_update_elementwise(self.m.cpu().numpy()[:, :P], self.ora.m[:, :P], np.zeros_like(m_old[:, :P]), f"{what} m")
+        if self.ld > P:
+            assert np.array_equal(self.x.cpu().numpy()[:, P:], x_old[:, P:]), f"{what}: padding columns of x changed"
 
     def check_state(self, tol, what="", tol_m=None):
         torch.cuda.synchronize()

@@ -7,7 +7,7 @@ import torch
 import oracle
 import workloads as wl
 import paper_1905_10395_amd as L
-from gpu_util import DEV, Pair, dev, rel_l2_rows
+from gpu_util import DEV, Pair, assert_update_elementwise, dev, rel_l2_rows
 from test_gpu_select_update import random_offsets
 
 pytestmark = pytest.mark.gpu
@@ -41,13 +41,13 @@ def test_leader_pull_matches_oracle(W, G, P, ld):
         if not rl.any() and not rg:
             rl[int(r.integers(0, G))] = 1
         pr.ora.losses[:] = losses
+        x_before = pr.ora.x.copy()
         pr.ora.select(rl, rg); pr.ora.leader_pull(lamL, lamG, rl, rg)
         pr.pop.select_leaders(dev(losses), rl, rg)
         pr.pop.leader_pull(lamL, lamG)
         assert pr.check_leaders(rl, rg)
         torch.cuda.synchronize()
-        ex = rel_l2_rows(pr.x.cpu().numpy()[:, :P], pr.ora.x[:, :P])
-        assert ex.max() <= 2e-7, (trial, ex.max())
+        assert_update_elementwise(pr.x.cpu().numpy()[:, :P], pr.ora.x[:, :P], x_before[:, :P], f"trial {trial}")
         Zg = pr.Z.cpu().numpy()
         for j in list(np.nonzero(rl)[0]) + ([G] if rg else []):
             np.testing.assert_array_equal(Zg[j, :P], pr.ora.Z[j, :P])
@@ -119,12 +119,18 @@ def test_step_alg1_external_gradients(W, G, P, ld, mu, staggered):
         losses = wl.stress_losses(W, t, seed=W + G)
         pr.set_grad(g, losses)
         rl, rg = wl.refresh_masks(t, tau, G, staggered=staggered, tau_G=tauG)
+        before = pr.follow_gpu()            # identical pre-iteration states: element-wise comparison
         alg1_oracle_iteration(pr.ora, eta, gamL, gamG, lamL, lamG, rl, rg)
         comm = (L.COMM_LOCAL if rl.any() else 0) | (L.COMM_GLOBAL if rg else 0)
         pr.pop.step_alg1(L.ExternalBatch(pr.losses_dev), eta, gamL, gamG, lamL, lamG, comm, rl)
-        assert pr.check_leaders(rl, rg)
-        pr.check_state(3e-4, f"iteration {t}", tol_m=3e-4)
-        assert rel_l2_rows(pr.Z.cpu().numpy()[:, :P], pr.ora.Z[:, :P]).max() < 3e-4
+        lead, gl = pr.pop.get_leaders()
+        assert lead == pr.ora.lead.tolist() and gl == int(pr.ora.glead[0])
+        # two or three chained fp32 updates per iteration (local step, local pull, global pull), each reading the
+        # previous one's rounded result: a few ulps of the value itself
+        pr.check_step_elementwise(before, f"iteration {t}", k_self=6.0)
+        # copies are taken after the local step, whose result differs in its last bits between the two sides
+        assert np.abs(pr.Z.cpu().numpy()[:, :P] - pr.ora.Z[:, :P]).max() <= 4 * np.finfo(np.float32).eps * np.abs(pr.ora.Z[:, :P]).max() + \
+            16 * np.finfo(np.float32).eps * np.abs(pr.ora.x[:, :P] - before[0][:, :P]).max()
 
 
 def test_step_alg1_matrix_completion():
