@@ -260,6 +260,36 @@ lsgd_status lsgd_get_leaders(lsgd_population* pop, int32_t* local_leaders, int32
 /* losses_host: host [W], the population's own loss buffer. */
 lsgd_status lsgd_get_losses(lsgd_population* pop, float* losses_host);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  One leader selection over all groups and
+ * the global leader followed by one pull update, i.e. what lsgd_step does for an
+ * LSGD_BATCH_EXTERNAL batch with a full refresh, without a population handle or workspace:
+ * the group table, leader indices and re-selection flags that the handle keeps in the
+ * caller's workspace live in a static device array inside the library (5 KB per GPU, held
+ * until the process ends), and the call itself allocates nothing on the host or the device.
+ *   W <= LSGD_STATIC_MAX_WORKERS, n_groups <= LSGD_STATIC_MAX_GROUPS: larger shapes are
+ *            rejected with LSGD_ERR_SHAPE
+ *   group_offsets host [n_groups+1] or NULL (equal groups), as in lsgd_config
+ *   x, g, m  device [W, ld] fp32 as in lsgd_create_population (m may be NULL when
+ *            momentum == 0); updated in place exactly as lsgd_pull_update does
+ *   losses   device [W]
+ *   leaders  device [n_groups+1] int32 or NULL: receives the local leaders and, last, the
+ *            global leader
+ *   flags    LSGD_NESTEROV | LSGD_LEADER_EXEMPT | LSGD_PULL_UNSCALED_BY_ETA |
+ *            LSGD_MOMENTUM_GRAD_ONLY
+ * Every leader is re-selected at every call, so no leader copies are kept.  Work is enqueued
+ * on hip_stream of the current device; nothing synchronises.  All calls on one GPU share
+ * that GPU's array: calls that may overlap there (different streams, different threads)
+ * race and must be ordered by the caller.  Every word a call reads it writes first, so the
+ * contents left by an earlier call never matter.                                          */
+#define LSGD_STATIC_MAX_WORKERS 1024
+#define LSGD_STATIC_MAX_GROUPS 64
+lsgd_status lsgd_select_pull_static(int32_t W, int64_t P, int64_t ld, int32_t n_groups,
+                                    const int32_t* group_offsets, float* x, const float* g, float* m,
+                                    const float* losses, int32_t* leaders, float eta, float lambda_L,
+                                    float lambda_G, float momentum, float weight_decay, int32_t flags,
+                                    void* hip_stream);
+
 /* Message for the last failing call on this thread ("" if none).  Static storage. */
 const char* lsgd_last_error(void);
 

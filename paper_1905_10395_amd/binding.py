@@ -89,6 +89,9 @@ def lib():
         L.lsgd_center.argtypes = [C.c_void_p, C.c_void_p]
         L.lsgd_sync_shadow.argtypes = [C.c_void_p]
         L.lsgd_mc_pack_entries.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        L.lsgd_select_pull_static.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
+                                              C.c_float, C.c_float, C.c_float, C.c_int32, C.c_void_p]
         L.lsgd_get_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.lsgd_get_losses.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         _lib = L
@@ -164,6 +167,21 @@ def workspace_bytes(W, P, ld, n_groups, group_offsets=None, momentum=0.0, flags=
     if n == 0:
         raise LsgdError(-1, lib().lsgd_last_error().decode())
     return n
+
+
+STATIC_MAX_WORKERS, STATIC_MAX_GROUPS = 1024, 64
+
+
+def select_pull_static(x, g, losses, n_groups, eta, lambda_L, lambda_G, m=None, P=None, group_offsets=None, momentum=0.0,
+                       weight_decay=0.0, flags=0, leaders=None, stream=None):
+    """lsgd_select_pull_static: selection over all groups + pull update with no handle, workspace or allocation.
+    x, g, m: float32 [W, ld]; losses: float32 [W]; leaders: optional int32 [n_groups+1] output."""
+    W, ld = x.shape
+    off = None if group_offsets is None else (C.c_int32 * len(group_offsets))(*[int(v) for v in group_offsets])
+    st = torch.cuda.current_stream(x.device) if stream is None else stream
+    _check(lib().lsgd_select_pull_static(W, ld if P is None else int(P), ld, int(n_groups), off, _ptr(x), _ptr(g), _ptr(m),
+                                         _ptr(losses), _ptr(leaders), eta, lambda_L, lambda_G, momentum, weight_decay,
+                                         int(flags), C.c_void_p(st.cuda_stream)))
 
 
 class Population:

@@ -14,10 +14,11 @@
 using namespace lsgd;
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
-lsgd_status fail(lsgd_status st, const char* fmt, ...)
+namespace lsgd {
+lsgd_status set_error(lsgd_status st, const char* fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
@@ -25,6 +26,11 @@ lsgd_status fail(lsgd_status st, const char* fmt, ...)
     va_end(ap);
     return st;
 }
+} // namespace lsgd
+
+namespace {
+
+#define fail(...) lsgd::set_error(__VA_ARGS__)
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }

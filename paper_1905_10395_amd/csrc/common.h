@@ -28,6 +28,9 @@ struct RefreshBits {
     uint64_t w[LSGD_MAX_GROUPS / 64];
 };
 
+// Records the message lsgd_last_error() returns on this thread and hands the status back.
+lsgd_status set_error(lsgd_status st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // ---- kernels' host launchers (each returns the hipError_t of its launches) ----
 hipError_t launch_init_state(const DeviceState& st, int W, int G, hipStream_t s);
 
