@@ -22,11 +22,16 @@
  * quadratic and the bound of Theorem 2; monotone leader value (Lemma
  * "leader_descent"); the sinc example's optimum -0.2172 (supplement Table 1);
  * grad F = (XX^T - M)X for the dense PSD problem; finite differences;
- * brute-force argmin; Algorithm 1's communication pull as two successive
- * single-leader interpolations; window mean and column mean against numpy.
+ * brute-force argmin and hand-computed near-tie gaps; momentum together with
+ * pulls against a library momentum-SGD fed the gradient of Eq. 2's objective
+ * with the leader copies held fixed (and, for the grad-only mode, fed g alone
+ * with the pulls as a plain step beside it), over stale periods; Algorithm
+ * 1's communication pull as two successive single-leader interpolations;
+ * window mean and column mean against numpy.
  *
- * Parity unpinned by the paper (fixed by declaration): where momentum enters
- * (heavy ball on the full direction by default), the bf16 rounding points of
+ * Fixed by declaration, the paper being silent (the arithmetic of each choice
+ * is pinned as above, the choice itself is not the paper's): that momentum is
+ * heavy ball on the full direction by default, the bf16 rounding points of
  * the MLP workload, the loss normalisation c of the matrix-completion batch.
  */
 #include <math.h>
@@ -59,8 +64,8 @@ static void argmin_range(const float* losses, int lo, int hi, int32_t* idx, doub
         double second = INFINITY;
         for (int i = lo; i < hi; ++i)
             if (i != best) { double v = sel_value(losses[i]); if (v < second) second = v; }
-        if (isinf(second) && isinf(bv)) *gap = 0.0;            /* all-infinite group: a tie */
-        else if (isinf(second)) *gap = INFINITY;               /* single finite member      */
+        if (second == bv) *gap = 0.0;                          /* a tie, also between infinities          */
+        else if (isinf(second) || isinf(bv)) *gap = INFINITY;  /* no finite runner-up, or a best of -inf  */
         else { double den = fabs(bv) > 1e-30 ? fabs(bv) : 1e-30; *gap = (second - bv) / den; }
     }
 }

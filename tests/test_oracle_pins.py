@@ -67,6 +67,48 @@ def test_select_honours_refresh_mask():
     assert lead.tolist() == [1, 3] and glead[0] == 3
 
 
+def test_gap_values_by_hand():
+    """The relative gap (second best - best)/|best| that the parity tests use to recognise a near-tie, on
+    losses whose gaps are known by hand.  Row G of the output is the global selection's gap."""
+    f = lambda *v: np.array(v, dtype=np.float32)
+    two = np.array([0, 2, 4], dtype=np.int32)
+
+    def gaps(losses, off, rl=None, rg=1):
+        G = len(off) - 1
+        return oracle.select_leaders(losses, off, np.zeros(G, np.int32), np.zeros(1, np.int32), rl, rg)
+
+    # plain positive losses: (3-2)/2 and (5-4)/4; globally (3-2)/2 again (best 2, second 3)
+    np.testing.assert_allclose(gaps(f(2, 3, 5, 4), two), [0.5, 0.25, 0.5], rtol=1e-12)
+    # negative best: (-1 - -2)/|-2| = 0.5, positive, not -0.5
+    np.testing.assert_allclose(gaps(f(-2, -1, -8, 0), two), [0.5, 1.0, 0.75], rtol=1e-12)
+    # exact ties (also -0 against +0) have gap 0
+    assert gaps(f(1, 1, -0.0, 0.0), two)[:2].tolist() == [0.0, 0.0]
+    # two losses one fp32 ulp apart: a near-tie far below the 1e-6 protocol threshold, but not zero
+    a = np.float32(1.0); b = np.nextafter(a, np.float32(2.0))
+    g = gaps(f(a, b, b, a), two)
+    np.testing.assert_allclose(g[:2], [float(b) - 1.0, float(b) - 1.0], rtol=1e-12)
+    assert 0.0 < g[0] < 1e-6 and g[2] == 0.0                    # globally, workers 0 and 3 tie exactly
+    # 1e-7 apart on a larger scale
+    np.testing.assert_allclose(gaps(f(100.0, 100.0 + 1e-5), one_group(2))[0], (float(np.float32(100.0 + 1e-5)) - 100.0) / 100.0, rtol=1e-12)
+    # a single finite member (NaN counts as +inf): nobody is close, gap is infinite
+    g = gaps(f(np.inf, 2, np.nan, 7), two)
+    assert g[0] == np.inf and g[1] == np.inf and np.isclose(g[2], 2.5)
+    # a group of infinities and NaN: every member ties
+    assert gaps(f(np.inf, np.nan, np.nan, np.nan), two).tolist() == [0.0, 0.0, 0.0]
+    # -inf best: |best| is infinite, a finite runner-up is infinitely far; two -inf tie
+    g = gaps(f(-np.inf, 1, -np.inf, -np.inf), two, rg=0)
+    assert g[0] == np.inf and g[1] == 0.0 and np.isnan(g[2])     # no global refresh: its gap is not reported
+    # a group of one worker has no runner-up
+    assert gaps(f(3), one_group(1)).tolist() == [np.inf, np.inf]
+    assert gaps(f(np.nan), one_group(1)).tolist() == [0.0, 0.0]
+    # best exactly zero: the denominator falls back to 1e-30, so any positive runner-up is far
+    g = gaps(f(0, 1e-3), one_group(2))
+    assert g[0] > 1e20
+    # groups left out of a refresh report nothing
+    g = gaps(f(2, 3, 5, 4), two, rl=np.array([0, 1], dtype=np.uint8), rg=0)
+    assert np.isnan(g[0]) and g[1] == 0.25 and np.isnan(g[2])
+
+
 # ----------------------------------------------------------------------------
 # Update: reductions to SGD (Eq. 3 with zero pulls) against torch.optim.SGD
 # ----------------------------------------------------------------------------
@@ -91,6 +133,55 @@ def test_zero_pull_is_per_worker_sgd(mu, nesterov, wd, grad_only):
         tx.grad = torch.tensor(g, dtype=torch.float64)
         opt.step()
     np.testing.assert_allclose(pop.x, tx.detach().numpy(), rtol=2e-6, atol=2e-7)
+
+
+@pytest.mark.parametrize("mu,nesterov,wd,grad_only", [
+    (0.9, False, 0.0, False), (0.9, True, 0.0, False), (0.7, True, 1e-2, False),
+    (0.9, False, 0.0, True), (0.5, True, 1e-2, True)])
+def test_momentum_with_pulls_is_momentum_sgd_on_the_pulled_objective(mu, nesterov, wd, grad_only):
+    """Heavy ball on the full direction is momentum-SGD applied to the objective of Eq. 2 with the leader
+    copies held fixed: feed torch.optim.SGD the augmented gradient g + lam_L (x - z_L) + lam_G (x - z_G).
+    With the pulls outside the buffer (grad-only mode) the optimizer sees g alone and the pulls, taken at the
+    pre-update point, are a plain step beside it.  Leaders, copies and refresh periods are tracked here
+    independently: refresh every 3 steps, global every 6, so stale copies (former leaders pulled to their own
+    old parameters) are covered."""
+    W, P = 6, 23
+    off = np.array([0, 2, 6], dtype=np.int32)
+    r = wl.stream("mom_pull_pin", int(mu * 10), int(nesterov), int(grad_only))
+    x0 = r.standard_normal((W, P)).astype(np.float32)
+    flags = (oracle.NESTEROV if nesterov else 0) | (oracle.MOMENTUM_GRAD_ONLY if grad_only else 0)
+    pop = oracle.Population(x0, off, momentum=mu, flags=flags, weight_decay=wd)
+    lr, lamL, lamG = 0.05, 0.3, 0.2
+    e, lL, lG = (float(np.float32(v)) for v in (lr, lamL, lamG))
+    tx = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([tx], lr=e, momentum=float(np.float32(mu)), nesterov=nesterov, weight_decay=float(np.float32(wd)))
+    zL = np.zeros((2, P)); zG = np.zeros(P)
+    group = np.array([0, 0, 1, 1, 1, 1])
+    for t in range(8):
+        g = r.standard_normal((W, P)).astype(np.float32)
+        losses = r.random(W, dtype=np.float32)
+        rl = np.array([t % 3 == 0, t % 3 == 0], dtype=np.uint8)
+        rg = int(t % 6 == 0)
+        pop.g[:] = g; pop.losses[:] = losses
+        pop.select(rl, rg); pop.update(lr, lamL, lamG, rl, rg)
+        # independent bookkeeping of leaders and their kept copies
+        xt = tx.detach().numpy().copy()
+        if rl[0]:
+            zL[0] = xt[int(np.argmin(losses[0:2]))]; zL[1] = xt[2 + int(np.argmin(losses[2:6]))]
+        if rg:
+            zG = xt[int(np.argmin(losses))].copy()
+        pulls = lL * (xt - zL[group]) + lG * (xt - zG)
+        if grad_only:
+            tx.grad = torch.tensor(g, dtype=torch.float64)
+            opt.step()
+            with torch.no_grad():
+                tx -= e * torch.tensor(pulls)
+        else:
+            tx.grad = torch.tensor(g + pulls, dtype=torch.float64)
+            opt.step()
+    np.testing.assert_allclose(pop.x, tx.detach().numpy(), rtol=2e-5, atol=2e-6)
+    # the pulls did something: the same run without them ends elsewhere
+    assert np.abs(pop.x - x0).max() > 0.1
 
 
 def test_leader_row_takes_a_pure_gradient_step():
