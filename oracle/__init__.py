@@ -111,6 +111,14 @@ def center(x, P, out):
     lib().lsgd_oracle_center(_f32(x), C.c_int(W), C.c_int64(int(P)), C.c_int64(int(ld)), _f32(out))
 
 
+def easgd_center(x, P, center, old_center, eta, lam):
+    """Elastic-averaging center update from the workers' current (pre-update) parameters, in place on
+    center[ld]; old_center[ld] receives the center as it was."""
+    W, ld = x.shape
+    lib().lsgd_oracle_easgd_center(_f32(x), C.c_int(W), C.c_int64(int(P)), C.c_int64(int(ld)), _f32(center), _f32(old_center),
+                                   C.c_float(eta), C.c_float(lam))
+
+
 def mc_grad_loss(x, m, n, r, rows, cols, vals, batch_idx, c, g, losses):
     """batch_idx: int32 [W,B] or None (every observed entry, for every worker)."""
     W, ld = x.shape
@@ -123,14 +131,16 @@ def mc_grad_loss(x, m, n, r, rows, cols, vals, batch_idx, c, g, losses):
                                    C.c_float(c), _f32(g), _f32(losses))
 
 
-def mlp_grad_loss(x, dims, X_bf16, y, g, losses):
-    """X_bf16: uint16 [W,B,d0] bf16 bit patterns; y: int32 [W,B]."""
+def mlp_grad_loss(x, dims, X_bf16, y, g, losses, min_abs_preact=None):
+    """X_bf16: uint16 [W,B,d0] bf16 bit patterns; y: int32 [W,B]; min_abs_preact: optional float32 [W,B] output,
+    per sample the smallest |pre-activation| over all hidden units (distance from a ReLU mask switch)."""
     W, ld = x.shape
     dims = np.ascontiguousarray(dims, dtype=np.int32)
     B = int(y.shape[1])
     assert X_bf16.dtype == np.uint16 and X_bf16.shape == (W, B, int(dims[0])) and X_bf16.flags.c_contiguous
     lib().lsgd_oracle_mlp_grad_loss(_f32(x), C.c_int(W), C.c_int64(int(ld)), C.c_int(len(dims) - 1), _i32(dims),
-                                    _p(X_bf16, C.c_uint16), _i32(y), C.c_int(B), _f32(g), _f32(losses))
+                                    _p(X_bf16, C.c_uint16), _i32(y), C.c_int(B), _f32(g), _f32(losses),
+                                    None if min_abs_preact is None else _f32(min_abs_preact))
 
 
 class Population:
@@ -160,14 +170,22 @@ class Population:
     def grad_loss_mc(self, prob_m, prob_n, r, rows, cols, vals, batch_idx, c):
         mc_grad_loss(self.x, prob_m, prob_n, r, rows, cols, vals, batch_idx, c, self.g, self.losses)
 
-    def grad_loss_mlp(self, dims, X_bf16, y):
-        mlp_grad_loss(self.x, dims, X_bf16, y, self.g, self.losses)
+    def grad_loss_mlp(self, dims, X_bf16, y, min_abs_preact=None):
+        mlp_grad_loss(self.x, dims, X_bf16, y, self.g, self.losses, min_abs_preact)
 
     def select(self, refresh_local=None, refresh_global=1):
         self.gaps = select_leaders(self.losses, self.off, self.lead, self.glead, refresh_local, refresh_global)
 
     def leader_pull(self, lam_L, lam_G, refresh_local=None, refresh_global=1):
         leader_pull(self.x, self.Z, self.P, self.off, self.lead, self.glead, lam_L, lam_G, refresh_local, refresh_global)
+
+    def easgd_update(self, center, eta, lam):
+        """Elastic averaging: center (float32 [ld], in place) moves towards the workers' mean, every worker
+        takes the pulled step towards the center as it was (the global row of Z is used for it)."""
+        easgd_center(self.x, self.P, center, self.Z[self.G], eta, lam)
+        none = np.zeros(self.G, dtype=np.uint8)
+        pull_update(self.x, self.m, self.g, self.Z, self.P, self.off, np.full(self.G, -1, np.int32), np.full(1, -1, np.int32),
+                    eta, 0.0, lam, self.mu, none, 0, self.flags & ~LEADER_EXEMPT, self.wd)
 
     def update(self, eta, lam_L, lam_G, refresh_local=None, refresh_global=1):
         pull_update(self.x, self.m, self.g, self.Z, self.P, self.off, self.lead, self.glead,

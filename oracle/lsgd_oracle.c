@@ -27,7 +27,10 @@
  * with the leader copies held fixed (and, for the grad-only mode, fed g alone
  * with the pulls as a plain step beside it), over stale periods; Algorithm
  * 1's communication pull as two successive single-leader interpolations;
- * window mean and column mean against numpy.
+ * window mean and column mean against numpy; the elastic-averaging comparison
+ * method against its printed optimum on the sinc example (-0.0912), its
+ * conserved sum, and the spurious stationary point of the supplement's
+ * proposition on EASGD.
  *
  * Fixed by declaration, the paper being silent (the arithmetic of each choice
  * is pinned as above, the choice itself is not the paper's): that momentum is
@@ -35,6 +38,7 @@
  * the MLP workload, the loss normalisation c of the matrix-completion batch.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -209,6 +213,28 @@ void lsgd_oracle_center(const float* x, int W, int64_t P, int64_t ld, float* out
     }
 }
 
+/* Elastic averaging (EAGD / EASGD), the method the paper compares with, in the form the supplement
+ * writes it beside LGD ("Low-Rank Matrix Completion Experiments"): every worker takes the same pulled
+ * step with the center in the leader's place, X+ = (1 - eta lam) X + eta lam Xc - eta grad, i.e.
+ * lsgd_oracle_pull_update with Z's global row holding the center and no local term; and the center
+ * moves to   Xc+ = (1 - p eta lam) Xc + p eta lam * (1/p) sum_i X^i   with p = W workers.
+ * Both formulas are read at the same time step: the mean is over the workers' parameters BEFORE
+ * their own update, so this function runs first (it only changes the center).  The pre-update
+ * center is returned in old_center for the workers' step.                                    */
+void lsgd_oracle_easgd_center(const float* x, int W, int64_t P, int64_t ld, float* center, float* old_center,
+                              float eta_f, float lam_f)
+{
+    const double a = (double)W * (double)eta_f * (double)lam_f;
+    for (int64_t p = 0; p < P; ++p) {
+        double s = 0.0;
+        for (int i = 0; i < W; ++i) s += (double)x[(int64_t)i * ld + p];
+        const double mean = s / (double)W;
+        const double c = (double)center[p];
+        old_center[p] = center[p];
+        center[p] = (float)((1.0 - a) * c + a * mean);
+    }
+}
+
 /* ------------------------------------------------------------------ */
 /* Matrix completion on observed entries.  Worker row = [U (m x r) | V (n x r)],
  * both row-major.  For batch entries k with (a_k, b_k, M_k):
@@ -276,15 +302,21 @@ static float bf16_bits_to_float(uint16_t b)
     uint32_t u = (uint32_t)b << 16; float o; memcpy(&o, &u, 4); return o;
 }
 
+/* min_abs_preact (optional, [W, B]): for every sample the smallest |z| over all hidden units of all hidden
+ * layers, i.e. how far the sample is from switching a ReLU mask.  A by-product of the forward pass for the
+ * tests; it takes no part in the arithmetic.
+ * Threads: over workers when there are at least as many workers as threads, otherwise over the independent
+ * outputs inside one worker (batch rows, or weight rows for dW); every sum keeps its order either way.   */
 void lsgd_oracle_mlp_grad_loss(const float* x, int W, int64_t ld, int n_layers, const int32_t* dims,
                                const uint16_t* X, const int32_t* y, int B,
-                               float* g, float* losses)
+                               float* g, float* losses, float* min_abs_preact)
 {
     const int L = n_layers;
     int64_t P = 0;
     for (int k = 0; k < L; ++k) P += (int64_t)dims[k + 1] * dims[k] + dims[k + 1];
+    const int over_workers = W >= omp_get_max_threads();
 
-    #pragma omp parallel for schedule(dynamic, 1)
+    #pragma omp parallel for schedule(dynamic, 1) if(over_workers)
     for (int i = 0; i < W; ++i) {
         const float* xi = x + (int64_t)i * ld;
         float* gi = g + (int64_t)i * ld;
@@ -313,6 +345,7 @@ void lsgd_oracle_mlp_grad_loss(const float* x, int W, int64_t ld, int n_layers, 
             int din = dims[k], dout = dims[k + 1];
             z[k + 1] = (float*)malloc(sizeof(float) * (size_t)B * dout);
             h[k + 1] = (float*)malloc(sizeof(float) * (size_t)B * dout);
+            #pragma omp parallel for schedule(static) if(!over_workers)
             for (int b = 0; b < B; ++b)
                 for (int q = 0; q < dout; ++q) {
                     double acc = 0.0;
@@ -324,6 +357,16 @@ void lsgd_oracle_mlp_grad_loss(const float* x, int W, int64_t ld, int n_layers, 
                     h[k + 1][(int64_t)b * dout + q] = (k + 1 < L) ? bf16_round(zz > 0.0f ? zz : 0.0f) : zz;
                 }
         }
+        if (min_abs_preact)
+            for (int b = 0; b < B; ++b) {
+                float mn = INFINITY;
+                for (int k = 1; k < L; ++k)
+                    for (int q = 0; q < dims[k]; ++q) {
+                        float a = fabsf(z[k][(int64_t)b * dims[k] + q]);
+                        if (a < mn) mn = a;
+                    }
+                min_abs_preact[(int64_t)i * B + b] = mn;
+            }
         /* loss and output delta */
         int C = dims[L];
         double loss = 0.0;
@@ -351,20 +394,24 @@ void lsgd_oracle_mlp_grad_loss(const float* x, int W, int64_t ld, int n_layers, 
             int64_t nw = (int64_t)din * dout;
             double* acc = (double*)calloc((size_t)nw, sizeof(double));
             double* accb = (double*)calloc((size_t)dout, sizeof(double));
-            for (int b = 0; b < B; ++b)
-                for (int q = 0; q < dout; ++q) {
+            /* dW[q][p] = sum_b delta[b][q] h[b][p], db[q] = sum_b delta[b][q]; b ascending in every sum */
+            #pragma omp parallel for schedule(static) if(!over_workers)
+            for (int q = 0; q < dout; ++q) {
+                double* ar = acc + (int64_t)q * din;
+                for (int b = 0; b < B; ++b) {
                     double d = delta[(int64_t)b * dout + q];
                     accb[q] += d;
                     if (d == 0.0) continue;
                     const float* hr = h[k] + (int64_t)b * din;
-                    double* ar = acc + (int64_t)q * din;
                     for (int p = 0; p < din; ++p) ar[p] += d * (double)hr[p];
                 }
+            }
             for (int64_t t = 0; t < nw; ++t) gi[woff[k] + t] = (float)acc[t];
             for (int q = 0; q < dout; ++q) gi[woff[k] + nw + q] = (float)accb[q];
             free(acc); free(accb);
             if (k > 0) {
                 float* nd = (float*)malloc(sizeof(float) * (size_t)B * din);
+                #pragma omp parallel for schedule(static) if(!over_workers)
                 for (int b = 0; b < B; ++b)
                     for (int p = 0; p < din; ++p) {
                         double s = 0.0;

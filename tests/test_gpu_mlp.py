@@ -91,6 +91,72 @@ def test_mlp_grad_loss_matches_oracle(dims, W, B):
     assert np.all(g[:, P:] == 0)
 
 
+def later_layer_wmax(x, dims):
+    """largest |weight| of the layers that read a quantised activation (all but the first)"""
+    off, w = dims[0] * dims[1] + dims[1], 0.0
+    for k in range(1, len(dims) - 1):
+        n = dims[k] * dims[k + 1]
+        w = max(w, float(np.abs(x[:, off:off + n]).max()))
+        off += n + dims[k + 1]
+    return w
+
+
+def margin_safe_batch(pr, dims, W, B, means, seed, oversample=4):
+    """A batch made of the samples that are farthest from a ReLU mask switch.  The oracle's forward pass over
+    oversample*B candidates per worker reports, per sample, the smallest |pre-activation| over all hidden units
+    (a sample's pre-activations do not depend on which other samples share its batch); the B candidates with
+    the largest such margin are kept.  Returns (X bits, y, smallest kept margin)."""
+    Xc, yc = wl.gmm_batch(W, oversample * B, means, 900, seed=seed)
+    margins = np.zeros((W, oversample * B), dtype=np.float32)
+    pr.ora.grad_loss_mlp(dims, Xc, yc, margins)
+    keep = np.sort(np.argsort(-margins, axis=1, kind="stable")[:, :B], axis=1)
+    rows = np.arange(W)[:, None]
+    return np.ascontiguousarray(Xc[rows, keep]), np.ascontiguousarray(yc[rows, keep]), float(margins[rows, keep].min())
+
+
+DEEP_SHAPES = [(d, W, B) for d, W, B in SHAPES if len(d) > 3] + [
+    ([3072, 512, 512, 10], 4, 256),           # K = 3072 first layer, then d-input at K = 512
+    ([3072, 512, 512, 512, 10], 4, 256),      # the 4-layer configuration's depth at width 512
+]
+
+
+@pytest.mark.parametrize("dims,W,B", DEEP_SHAPES)
+def test_deep_mlp_grads_tight_on_margin_safe_batches(dims, W, B):
+    """Nets with several hidden layers held to the single-hidden-layer bar.  What separates the two sides on a
+    deep net is a ReLU unit whose pre-activation lies so close to zero that an upstream activation differing by
+    one bf16 ulp (2^-8 of a value of order one) times a weight flips its sign.  The batch is therefore built
+    from samples the oracle certifies to be farther than that from any switch: every kept sample has
+    min |z| >= 2^-8 * max|w| over all hidden units.  On such a batch both sides take the same mask decisions and
+    what is left is the rounding of bf16 operands, as with one hidden layer: median worker 1e-4 (per
+    requantisation of the deltas on their way back), every worker 2e-3 per parameter block.  Every deep-only code path (d-input products, transposed delta copies at
+    K = hidden width, the 256x128 tile) is in these shapes."""
+    pr, _, _, _, P, means = make(dims, W, B, seed=len(dims) * 100 + W)
+    Xb, y, margin = margin_safe_batch(pr, dims, W, B, means, seed=len(dims) * 100 + W, oversample=6 if dims[0] > 1000 else 4)
+    assert margin >= later_layer_wmax(pr.ora.x, dims) / 256.0, margin
+    batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+    pr.g.fill_(7.0)
+    pr.ora.grad_loss_mlp(dims, Xb, y)
+    pr.pop.grad_loss(batch)
+    torch.cuda.synchronize()
+    g = pr.g.cpu().numpy()
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
+    med, mx = per_layer_errors(g[:, :P], pr.ora.g[:, :P], dims)
+    # each requantisation of the back-propagated deltas adds its own share of values that round to the other
+    # bf16 neighbour (measured: 6e-5 median with two hidden layers, 1.2e-4 with three): 1e-4 per requantisation
+    requant = max(1, len(dims) - 3)
+    assert max(med) < GRAD_TOL_MEDIAN * requant, [float(f"{v:.2e}") for v in med]
+    assert max(mx) < GRAD_TOL_MAX, [float(f"{v:.2e}") for v in mx]
+    assert np.all(g[:, P:] == 0)
+
+
+def check_m_like_gradient(pr, dims):
+    """After one step from m = 0 the momentum buffer is the gradient plus the pulls: the gradient's bar."""
+    P = pr.P
+    med, mx = per_layer_errors(pr.m.cpu().numpy()[:, :P], pr.ora.m[:, :P], dims)
+    assert max(med) < GRAD_TOL_MEDIAN, med
+    assert max(mx) < GRAD_TOL_MAX, mx
+
+
 def test_mlp_lsgd_steps_with_momentum_and_shadow():
     """16 workers in 4 groups, momentum 0.9, lam_L 0.1, lam_G 0.05, leaders every step; the bf16 operands
     of step t+1 come from the shadow written by the update of step t."""
@@ -127,8 +193,9 @@ def test_mlp_two_layer_config_full_size_one_step():
     np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
     check_grads(pr.g.cpu().numpy()[:, :P], pr.ora.g[:, :P], dims)
     # parameters to 1e-4; the momentum buffer after one step is the gradient plus pulls, so it
-    # inherits the gradient's tolerance
+    # is held to the gradient's own bar (typical worker 1e-4, no worker beyond 2e-3), block by block
     pr.check_state(1e-4, "full-size step", tol_m=GRAD_TOL_MAX)
+    check_m_like_gradient(pr, dims)
 
 
 def test_mlp_four_layer_staggered_refresh_steps():
@@ -148,7 +215,7 @@ def test_mlp_four_layer_staggered_refresh_steps():
         if not pr.check_leaders(rl, rg):
             pr.resync_from_oracle()
         if t == 0:
-            np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=3e-4)
+            np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
             check_grads(pr.g.cpu().numpy()[:, :P], pr.ora.g[:, :P], dims)
             pr.check_state(1e-4, "step 0", tol_m=DEEP_TOL)
     np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-3)
@@ -195,7 +262,7 @@ def test_fused_update_steps(dims, W, G, B, mu, flags, wd):
         if not pr.check_leaders(rl, rg):
             pr.resync_from_oracle()
             pr.pop.sync_shadow()
-        np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=3e-4 if t == 0 else 1e-3)
+        np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4 if t == 0 else 1e-3)
         # the momentum buffer carries the gradient's own tolerance (one switched ReLU unit per worker, see above);
         # from the second step on the two sides start from states up to 1e-3 apart, so allow a few such units
         pr.check_state(1e-4 if t == 0 else 1e-3, f"step {t}",
@@ -253,6 +320,64 @@ def test_fused_update_two_layer_config_full_size_one_step():
     assert pr.check_leaders()
     np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=1e-4)
     pr.check_state(1e-4, "full-size fused step", tol_m=GRAD_TOL_MAX)
+    check_m_like_gradient(pr, dims)
+
+
+def test_four_layer_config_full_size_two_workers_against_oracle():
+    """3072-4096-4096-4096-10, W=8 in 2 groups of 4, batch 256, momentum 0.9, lam_L 0.1, lam_G 0.02 at full
+    size on the GPU.  Gradients are independent per worker, so the oracle (64.5 GFLOP per worker) runs two of
+    the eight workers, one from each group: their losses to 1e-4, their gradients per parameter block at the
+    deep-net bar (this batch is the configuration's own, not selected for margins), and their rows after the
+    whole fused step against the oracle's update fed the same leader rows."""
+    dims, W, G, B = [3072, 4096, 4096, 4096, 10], 8, 2, 256
+    P = wl.mlp_param_count(dims)
+    ld = wl.padded_ld(P)
+    gen = torch.Generator(device=DEV).manual_seed(17)
+    x = torch.empty((W, ld), device=DEV)
+    off = 0
+    for k in range(len(dims) - 1):                          # U(+-fan_in^-1/2) weights, zero biases, as in the workload recipe
+        n = dims[k + 1] * dims[k]
+        x[:, off:off + n].uniform_(-dims[k] ** -0.5, dims[k] ** -0.5, generator=gen)
+        x[:, off + n:off + n + dims[k + 1]] = 0
+        off += n + dims[k + 1]
+    x[:, P:] = 0
+    means = wl.gmm_means(dims[0], dims[-1], seed=17)
+    Xb, y = wl.gmm_batch(W, B, means, 0, seed=17)
+    batch = L.MLPBatch(dims, dev(Xb.view(np.int16)).view(torch.bfloat16), dev(y))
+    g = torch.zeros_like(x); m = torch.zeros_like(x)
+    Z = torch.zeros((G + 1, ld), device=DEV)
+    xb = torch.zeros((W, ld), dtype=torch.bfloat16, device=DEV)
+    pop = L.Population(x, g, G, m=m, z_snapshot=Z, x_bf16=xb, P=P, momentum=0.9, flags=L.FUSED_MLP_UPDATE, largest_batch=batch)
+    sample = [1, 6]
+    x_old = x[sample].cpu().numpy()
+    ora = oracle.Population(x_old, np.array([0, 1, 2], dtype=np.int32), momentum=0.9, P=P)
+    ora.grad_loss_mlp(dims, np.ascontiguousarray(Xb[sample]), np.ascontiguousarray(y[sample]))
+    # gradients and losses through the separate call
+    pop.grad_loss(batch)
+    losses = np.array(pop.get_losses())
+    np.testing.assert_allclose(losses[sample], ora.losses, rtol=1e-4)
+    med, mx = per_layer_errors(g[sample].cpu().numpy()[:, :P], ora.g[:, :P], dims)
+    assert max(mx) < DEEP_TOL, mx
+    assert torch.count_nonzero(g[:, P:]) == 0
+    # the whole step with the update applied inside the backward kernels
+    lead_want = [int(np.argmin(losses[0:4])), 4 + int(np.argmin(losses[4:8]))]
+    gl_want = int(np.argmin(losses))
+    z_rows = x[lead_want + [gl_want]].cpu().numpy()          # the leaders' parameters before the step
+    pop.step(batch, 0.01, 0.1, 0.02)
+    lead, gl = pop.get_leaders()
+    assert lead == lead_want and gl == gl_want
+    np.testing.assert_allclose(np.array(pop.get_losses())[sample], ora.losses, rtol=1e-4)
+    ora.Z[:] = z_rows                                       # worker 1 pulls to Z[0] and Z[2], worker 6 to Z[1] and Z[2]
+    ora.lead[:] = [-1, -1]; ora.glead[0] = -1               # (indices only matter to the leader-exempt flag)
+    none = np.zeros(2, dtype=np.uint8)
+    ora.update(0.01, 0.1, 0.02, none, 0)
+    torch.cuda.synchronize()
+    ex = rel_l2_rows(x[sample].cpu().numpy()[:, :P], ora.x[:, :P])
+    assert ex.max() <= 1e-4, ex
+    em = rel_l2_rows(m[sample].cpu().numpy()[:, :P], ora.m[:, :P])
+    assert em.max() <= DEEP_TOL, em
+    np.testing.assert_array_equal(Z.cpu().numpy()[:, :P], z_rows[:, :P])
+    assert torch.equal(xb[:, :P], x[:, :P].to(torch.bfloat16))
 
 
 def test_fused_update_four_layer_full_size_matches_three_call_step():
