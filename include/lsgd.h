@@ -173,7 +173,8 @@ lsgd_status lsgd_grad_loss(lsgd_population* pop, const lsgd_batch* batch, float*
  * index attaining the minimum over all workers.  NaN counts as +infinity.  The
  * leaders refreshed here are captured (copied from x before any row changes) by
  * the next lsgd_pull_update; the others keep their stored copies.
- * losses: device [W]; NULL = the population's own buffer.                       */
+ * losses: device [W]; NULL = the population's own buffer (LSGD_ERR_STATE if
+ * nothing has written it yet).                                                  */
 lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses,
                                 const uint8_t* refresh_local, int refresh_global);
 
@@ -182,7 +183,10 @@ lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses,
  * In place on x and m; every row is computed from pre-update values.  A term
  * whose coefficient is exactly 0 is skipped and its leader copy is neither read
  * nor written.  LSGD_ERR_STATE if a needed leader was never selected, or a kept
- * copy is needed and z_snapshot is NULL.                                        */
+ * copy is needed and z_snapshot is NULL.  A leader re-selected since the last
+ * update whose coefficient is 0 in this call is not captured; its kept copy is
+ * then no longer valid (LSGD_ERR_STATE for a later update that would need it
+ * before the next selection).                                                   */
 lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, float lambda_G);
 
 /* grad_loss -> select_leaders -> pull_update with the population's own loss
@@ -244,6 +248,21 @@ lsgd_status lsgd_smooth_losses(lsgd_population* pop, float* window, int32_t K, i
  * fast path), must not overlap x.                                              */
 lsgd_status lsgd_center(lsgd_population* pop, float* out);
 
+/* Elastic averaging (EAGD / EASGD), the method the paper compares with, as a variant of the same update
+ * (supplement, "Low-Rank Matrix Completion Experiments": both methods are X+ = (1 - eta lam) X + eta lam Z -
+ * eta grad, with Z the leader for LGD and the center for EAGD):
+ *   center+ = (1 - W eta lam) center + W eta lam * (1/W) sum_i x_i       (mean in double, rounded once)
+ *   x_i+    = x_i - eta (g_i + lam (x_i - center))                        for every worker,
+ * both from the values before the call; momentum, weight decay and the Nesterov / grad-only flags of the
+ * population apply to the workers' step as in lsgd_pull_update; no leaders are involved.
+ *   center device [ld] fp32 owned by the caller (16-byte aligned for the fast path), updated in place; the
+ *          caller initialises it (the paper does not say how; e.g. with lsgd_center)
+ * The pre-update center is kept in the global row of z_snapshot during the call, which therefore must exist
+ * and afterwards no longer holds a global leader copy.  LSGD_ERR_STATE while a leader selection is pending.
+ * lsgd_easgd_step = lsgd_grad_loss into the population's own buffers, then lsgd_easgd_update.            */
+lsgd_status lsgd_easgd_update(lsgd_population* pop, float* center, float eta, float lambda);
+lsgd_status lsgd_easgd_step(lsgd_population* pop, const lsgd_batch* batch, float* center, float eta, float lambda);
+
 /* Builds the 16-byte-record form of an observed-entry list (device to device, on
  * hip_stream): out[k] = {rows[k], cols[k], vals[k], 0}.  The list of observed
  * entries is fixed across steps (the paper's M and its observed set), so this is
@@ -257,6 +276,12 @@ lsgd_status lsgd_sync_shadow(lsgd_population* pop);
 /* Synchronise the stream and read back.  local_leaders: host [n_groups];
  * global_leader: host [1]; either may be NULL.  Leaders never selected read -1. */
 lsgd_status lsgd_get_leaders(lsgd_population* pop, int32_t* local_leaders, int32_t* global_leader);
+/* Restores leader indices read earlier with lsgd_get_leaders (checkpoint / resume: the state of a run is
+ * x, m, z_snapshot and these G+1 indices; x_bf16 is rebuilt from x by the next gradient call).  The rows of
+ * z_snapshot are taken to be the copies that belong to these leaders, no re-selection is pending afterwards.
+ * local_leaders: host [n_groups], each a row of its group or -1 (never selected); global_leader: a row or -1.
+ * Synchronises the stream.                                                                                */
+lsgd_status lsgd_set_leaders(lsgd_population* pop, const int32_t* local_leaders, int32_t global_leader);
 /* losses_host: host [W], the population's own loss buffer. */
 lsgd_status lsgd_get_losses(lsgd_population* pop, float* losses_host);
 

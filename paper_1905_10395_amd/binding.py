@@ -87,6 +87,8 @@ def lib():
                                      C.c_int, C.POINTER(C.c_uint8)]
         L.lsgd_smooth_losses.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p]
         L.lsgd_center.argtypes = [C.c_void_p, C.c_void_p]
+        L.lsgd_easgd_update.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_float]
+        L.lsgd_easgd_step.argtypes = [C.c_void_p, C.POINTER(_Batch), C.c_void_p, C.c_float, C.c_float]
         L.lsgd_sync_shadow.argtypes = [C.c_void_p]
         L.lsgd_mc_pack_entries.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         L.lsgd_select_pull_static.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
@@ -94,6 +96,7 @@ def lib():
                                               C.c_float, C.c_float, C.c_float, C.c_int32, C.c_void_p]
         L.lsgd_get_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.lsgd_get_losses.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
+        L.lsgd_set_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
         _lib = L
     return _lib
 
@@ -257,6 +260,14 @@ class Population:
         assert out.dtype == torch.float32 and out.is_contiguous() and out.numel() >= self.P
         _check(lib().lsgd_center(self._h, _ptr(out)))
 
+    def easgd_update(self, center, eta, lam):
+        assert center.dtype == torch.float32 and center.is_contiguous() and center.numel() >= self.ld
+        _check(lib().lsgd_easgd_update(self._h, _ptr(center), eta, lam))
+
+    def easgd_step(self, batch, center, eta, lam):
+        assert center.dtype == torch.float32 and center.is_contiguous() and center.numel() >= self.ld
+        _check(lib().lsgd_easgd_step(self._h, C.byref(batch.c), _ptr(center), eta, lam))
+
     def sync_shadow(self):
         _check(lib().lsgd_sync_shadow(self._h))
 
@@ -265,6 +276,10 @@ class Population:
         gl = C.c_int32()
         _check(lib().lsgd_get_leaders(self._h, lead, C.byref(gl)))
         return list(lead), int(gl.value)
+
+    def set_leaders(self, local_leaders, global_leader):
+        arr = (C.c_int32 * self.G)(*[int(v) for v in local_leaders])
+        _check(lib().lsgd_set_leaders(self._h, arr, int(global_leader)))
 
     def get_losses(self):
         out = (C.c_float * self.W)()

@@ -152,6 +152,7 @@ struct lsgd_population {
     std::vector<uint8_t> local_selected, pending_local, z_valid; // z_valid: [G+1]
     bool global_selected, pending_global;
     bool shadow_valid;
+    bool losses_valid; // the population's own loss buffer has been written (grad_loss / smooth_losses into it)
     int group_size; // rows per group if all groups are equal, else 0
 };
 
@@ -216,6 +217,7 @@ lsgd_status lsgd_create_population(const lsgd_config* cfg, float* x, float* g, f
     p->z_valid.assign((size_t)cfg->n_groups + 1, 0);
     p->global_selected = p->pending_global = false;
     p->shadow_valid = false;
+    p->losses_valid = false;
     p->group_size = off[1] - off[0];
     for (int j = 0; j < cfg->n_groups; ++j)
         if (off[(size_t)j + 1] - off[(size_t)j] != off[1] - off[0]) p->group_size = 0;
@@ -281,6 +283,7 @@ lsgd_status do_grad_loss(lsgd_population* p, const lsgd_batch* batch, float* los
     default: break;
     }
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "grad_loss: %s", hipGetErrorString(e));
+    if (!losses_out) p->losses_valid = true;
     return LSGD_OK;
 }
 
@@ -383,11 +386,13 @@ lsgd_status do_pull(lsgd_population* p, float eta, float lamL, float lamG, bool 
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "%s: %s", comm ? "leader_pull" : "pull_update", hipGetErrorString(e));
     // a refreshed leader whose term was active has now been captured (and kept, if Z exists);
     // the communication pull captures every refreshed leader
+    // (a re-selected leader whose coefficient was exactly 0 was not captured: its kept copy, if any, still
+    // belongs to the previous leader, so it stops being valid until the next selection)
     for (int j = 0; j < G; ++j) {
-        if (p->pending_local[(size_t)j] && (comm || lamL != 0.0f)) p->z_valid[(size_t)j] = p->Z != nullptr;
+        if (p->pending_local[(size_t)j]) p->z_valid[(size_t)j] = (comm || lamL != 0.0f) && p->Z != nullptr;
         p->pending_local[(size_t)j] = 0;
     }
-    if (p->pending_global && (comm || lamG != 0.0f)) p->z_valid[(size_t)G] = p->Z != nullptr;
+    if (p->pending_global) p->z_valid[(size_t)G] = (comm || lamG != 0.0f) && p->Z != nullptr;
     p->pending_global = false;
     if (!(p->cfg.flags & LSGD_WRITE_BF16_SHADOW)) p->shadow_valid = false;
     return LSGD_OK;
@@ -412,15 +417,17 @@ lsgd_status do_fused_mlp_step(lsgd_population* p, const lsgd_batch* batch, float
     }
     e = launch_mlp_forward(p->xb, p->x, p->st.losses, p->cfg.W, p->cfg.P, p->cfg.ld, *d, p->st, p->stream);
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "mlp forward: %s", hipGetErrorString(e));
+    p->losses_valid = true;
     lsgd_status st = do_select(p, nullptr, refresh_local, refresh_global);
     if (st != LSGD_OK) return st;
     if (any_pending(p)) {
         if (lamL != 0.0f || lamG != 0.0f) {
             st = do_pull(p, 0.0f, 0.0f, 0.0f, false, true);            // capture only: nobody moves
             if (st != LSGD_OK) return st;
-        } else {
-            std::fill(p->pending_local.begin(), p->pending_local.end(), (uint8_t)0);
-            p->pending_global = false;
+        } else {                                                       // nothing is captured: old copies go stale
+            for (int j = 0; j < p->cfg.n_groups; ++j)
+                if (p->pending_local[(size_t)j]) { p->z_valid[(size_t)j] = 0; p->pending_local[(size_t)j] = 0; }
+            if (p->pending_global) { p->z_valid[(size_t)p->cfg.n_groups] = 0; p->pending_global = false; }
         }
     }
     FusedUpdate fu{};
@@ -454,6 +461,9 @@ lsgd_status lsgd_grad_loss(lsgd_population* pop, const lsgd_batch* batch, float*
 lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses, const uint8_t* refresh_local, int refresh_global)
 {
     if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!losses && !pop->losses_valid)
+        return fail(LSGD_ERR_STATE, "select_leaders: losses is NULL and the population's own loss buffer was never written "
+                                    "(no lsgd_grad_loss / lsgd_smooth_losses into it yet)");
     return do_select(pop, losses, refresh_local, refresh_global);
 }
 
@@ -538,9 +548,12 @@ lsgd_status lsgd_smooth_losses(lsgd_population* pop, float* window, int32_t K, i
     if (!window) return fail(LSGD_ERR_INVALID_ARG, "smooth_losses: window is NULL");
     if (K <= 0 || K > 65536) return fail(LSGD_ERR_SHAPE, "smooth_losses: K = %d outside [1, 65536]", (int)K);
     if (t < 0) return fail(LSGD_ERR_INVALID_ARG, "smooth_losses: t is negative");
+    if (!losses && !pop->losses_valid)
+        return fail(LSGD_ERR_STATE, "smooth_losses: losses is NULL and the population's own loss buffer was never written");
     hipError_t e = launch_smooth_losses(window, K, t, losses ? losses : pop->st.losses, pop->cfg.W,
                                         out ? out : pop->st.losses, pop->stream);
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "smooth_losses: %s", hipGetErrorString(e));
+    if (!out) pop->losses_valid = true;
     return LSGD_OK;
 }
 
@@ -551,6 +564,51 @@ lsgd_status lsgd_center(lsgd_population* pop, float* out)
     hipError_t e = launch_center(pop->x, pop->cfg.W, pop->cfg.P, pop->cfg.ld, out, pop->stream);
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "center: %s", hipGetErrorString(e));
     return LSGD_OK;
+}
+
+lsgd_status lsgd_easgd_update(lsgd_population* pop, float* center, float eta, float lambda)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!center) return fail(LSGD_ERR_INVALID_ARG, "easgd_update: center is NULL");
+    lsgd_status st = check_scalars(eta, lambda, 0.0f);
+    if (st != LSGD_OK) return st;
+    if (!pop->Z) return fail(LSGD_ERR_STATE, "easgd_update keeps the pre-update center in z_snapshot, which is NULL");
+    if (any_pending(pop)) return fail(LSGD_ERR_STATE, "easgd_update: a leader selection is pending; elastic averaging uses no leaders");
+    const int G = pop->cfg.n_groups;
+    // center first (it reads the workers before they move); the old center lands in the global row of Z
+    const double a = (double)pop->cfg.W * (double)eta * (double)lambda;
+    hipError_t e = launch_easgd_center(pop->x, pop->cfg.W, pop->cfg.P, pop->cfg.ld, center, pop->Z + (int64_t)G * pop->cfg.ld, a, pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "easgd_update: center: %s", hipGetErrorString(e));
+    pop->z_valid[(size_t)G] = 0;             // that row no longer holds a leader
+    PullParams q;
+    q.x = pop->x; q.g = pop->g; q.m = pop->m; q.Z = pop->Z;
+    q.xb = (pop->cfg.flags & LSGD_WRITE_BF16_SHADOW) ? pop->xb : nullptr;
+    q.P = pop->cfg.P; q.ld = pop->cfg.ld; q.W = pop->cfg.W; q.G = G;
+    q.eta = eta; q.mu = pop->cfg.momentum; q.wd = pop->cfg.weight_decay;
+    q.lamL = 0.0f; q.lamG = lambda;
+    q.flags = pop->cfg.flags & ~LSGD_LEADER_EXEMPT;        // nobody is a leader here
+    q.use_refreshed = 0; q.clear_refreshed = 0;
+    q.group_size = pop->group_size;
+    q.comm_pull = 0;
+    e = launch_pull_update(q, pop->st, pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "easgd_update: %s", hipGetErrorString(e));
+    if (!(pop->cfg.flags & LSGD_WRITE_BF16_SHADOW)) pop->shadow_valid = false;
+    return LSGD_OK;
+}
+
+lsgd_status lsgd_easgd_step(lsgd_population* pop, const lsgd_batch* batch, float* center, float eta, float lambda)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!center) return fail(LSGD_ERR_INVALID_ARG, "easgd_step: center is NULL");
+    lsgd_status st = check_scalars(eta, lambda, 0.0f);
+    if (st != LSGD_OK) return st;
+    if (!pop->Z) return fail(LSGD_ERR_STATE, "easgd_step keeps the pre-update center in z_snapshot, which is NULL");
+    if (any_pending(pop)) return fail(LSGD_ERR_STATE, "easgd_step: a leader selection is pending; elastic averaging uses no leaders");
+    st = check_grad_loss(pop, batch);
+    if (st != LSGD_OK) return st;
+    st = do_grad_loss(pop, batch, nullptr);
+    if (st != LSGD_OK) return st;
+    return lsgd_easgd_update(pop, center, eta, lambda);
 }
 
 lsgd_status lsgd_mc_pack_entries(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n_obs,
@@ -585,6 +643,36 @@ lsgd_status lsgd_get_leaders(lsgd_population* pop, int32_t* local_leaders, int32
         e = hipMemcpyAsync(global_leader, pop->st.glead, sizeof(int32_t), hipMemcpyDeviceToHost, pop->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(pop->stream);
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "get_leaders: %s", hipGetErrorString(e));
+    return LSGD_OK;
+}
+
+lsgd_status lsgd_set_leaders(lsgd_population* pop, const int32_t* local_leaders, int32_t global_leader)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    if (!local_leaders) return fail(LSGD_ERR_INVALID_ARG, "set_leaders: local_leaders is NULL");
+    const int G = pop->cfg.n_groups;
+    for (int j = 0; j < G; ++j) {
+        const int32_t v = local_leaders[j];
+        if (v != -1 && (v < pop->offsets[(size_t)j] || v >= pop->offsets[(size_t)j + 1]))
+            return fail(LSGD_ERR_INVALID_ARG, "set_leaders: leader %d is not a row of group %d", (int)v, j);
+    }
+    if (global_leader != -1 && (global_leader < 0 || global_leader >= pop->cfg.W))
+        return fail(LSGD_ERR_INVALID_ARG, "set_leaders: global leader %d outside [0, W)", (int)global_leader);
+    // staged through the host object so that the source outlives the asynchronous copy
+    std::vector<int32_t> stage(local_leaders, local_leaders + G);
+    stage.push_back(global_leader);
+    hipError_t e = hipMemcpyAsync(pop->st.lead, stage.data(), sizeof(int32_t) * (size_t)G, hipMemcpyHostToDevice, pop->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(pop->st.glead, stage.data() + G, sizeof(int32_t), hipMemcpyHostToDevice, pop->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(pop->stream);
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "set_leaders: %s", hipGetErrorString(e));
+    for (int j = 0; j < G; ++j) {
+        pop->local_selected[(size_t)j] = stage[(size_t)j] != -1;
+        pop->pending_local[(size_t)j] = 0;
+        pop->z_valid[(size_t)j] = stage[(size_t)j] != -1 && pop->Z != nullptr;
+    }
+    pop->global_selected = global_leader != -1;
+    pop->pending_global = false;
+    pop->z_valid[(size_t)G] = global_leader != -1 && pop->Z != nullptr;
     return LSGD_OK;
 }
 

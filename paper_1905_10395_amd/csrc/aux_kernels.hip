@@ -66,6 +66,71 @@ __global__ __launch_bounds__(kCenterThreads) void center_kernel(const float* __r
     }
 }
 
+// Elastic-averaging center (the comparison method of the paper, supplement "Low-Rank Matrix Completion
+// Experiments"): center <- (1 - a) center + a * mean_i x[i], a = W*eta*lambda, with the mean taken in
+// double in row order as above; the center as it was goes to old_center (the workers' step pulls to it).
+// In place on center: a thread reads its columns of center before it writes them.
+template <int VEC>
+__global__ __launch_bounds__(kCenterThreads) void easgd_center_kernel(const float* __restrict__ x, int W, int64_t col0, int64_t col1,
+                                                                      int64_t ld, float* __restrict__ center,
+                                                                      float* __restrict__ old_center, double a)
+{
+#pragma clang fp contract(off)      // (1-a)*c + a*mean as two products and a sum, rounded like the plain expression
+    const int64_t col = col0 + ((int64_t)blockIdx.x * kCenterThreads + threadIdx.x) * VEC;
+    if (col >= col1) return;
+    double s[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) s[v] = 0.0;
+    const float* p = x + col;
+    int i = 0;
+    if (VEC == 4) {
+        const v4f c = *reinterpret_cast<const v4f*>(center + col);
+        for (; i + kRows <= W; i += kRows) {
+            v4f r[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) r[u] = *reinterpret_cast<const v4f*>(p + (int64_t)(i + u) * ld);
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                s[0] += (double)r[u].x; s[1 % VEC] += (double)r[u].y; s[2 % VEC] += (double)r[u].z; s[3 % VEC] += (double)r[u].w;
+            }
+        }
+        for (; i < W; ++i) {
+            const v4f r = *reinterpret_cast<const v4f*>(p + (int64_t)i * ld);
+            s[0] += (double)r.x; s[1 % VEC] += (double)r.y; s[2 % VEC] += (double)r.z; s[3 % VEC] += (double)r.w;
+        }
+        v4f o;
+        o.x = (float)((1.0 - a) * (double)c.x + a * (s[0] / (double)W));
+        o.y = (float)((1.0 - a) * (double)c.y + a * (s[1 % VEC] / (double)W));
+        o.z = (float)((1.0 - a) * (double)c.z + a * (s[2 % VEC] / (double)W));
+        o.w = (float)((1.0 - a) * (double)c.w + a * (s[3 % VEC] / (double)W));
+        *reinterpret_cast<v4f*>(old_center + col) = c;
+        *reinterpret_cast<v4f*>(center + col) = o;
+    } else {
+        const float c = center[col];
+        for (; i < W; ++i) s[0] += (double)p[(int64_t)i * ld];
+        old_center[col] = c;
+        center[col] = (float)((1.0 - a) * (double)c + a * (s[0] / (double)W));
+    }
+}
+
+hipError_t launch_easgd_center(const float* x, int W, int64_t P, int64_t ld, float* center, float* old_center, double a, hipStream_t s)
+{
+    auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
+    const bool vec_ok = (ld % 4 == 0) && aligned16(x) && aligned16(center) && aligned16(old_center);
+    const int64_t P4 = vec_ok ? (P & ~(int64_t)3) : 0;
+    if (P4 > 0) {
+        const int64_t blocks = (P4 / 4 + kCenterThreads - 1) / kCenterThreads;
+        hipLaunchKernelGGL((easgd_center_kernel<4>), dim3((unsigned)blocks), dim3(kCenterThreads), 0, s, x, W, (int64_t)0, P4, ld, center,
+                           old_center, a);
+    }
+    if (P > P4) {
+        const int64_t blocks = (P - P4 + kCenterThreads - 1) / kCenterThreads;
+        hipLaunchKernelGGL((easgd_center_kernel<1>), dim3((unsigned)blocks), dim3(kCenterThreads), 0, s, x, W, P4, P, ld, center,
+                           old_center, a);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_smooth_losses(float* window, int K, int64_t t, const float* losses, int W, float* out, hipStream_t s)
 {
     const int slot = (int)(t % K);

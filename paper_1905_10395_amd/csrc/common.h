@@ -56,6 +56,7 @@ struct PullParams {
 hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s);
 
 hipError_t launch_smooth_losses(float* window, int K, int64_t t, const float* losses, int W, float* out, hipStream_t s);
+hipError_t launch_easgd_center(const float* x, int W, int64_t P, int64_t ld, float* center, float* old_center, double a, hipStream_t s);
 hipError_t launch_center(const float* x, int W, int64_t P, int64_t ld, float* out, hipStream_t s);
 
 hipError_t launch_cast_shadow(const float* x, uint16_t* xb, int W, int64_t P, int64_t ld, hipStream_t s);
