@@ -290,7 +290,7 @@ lsgd_status lsgd_get_losses(lsgd_population* pop, float* losses_host);
  * the global leader followed by one pull update, i.e. what lsgd_step does for an
  * LSGD_BATCH_EXTERNAL batch with a full refresh, without a population handle or workspace:
  * the group table, leader indices and re-selection flags that the handle keeps in the
- * caller's workspace live in a static device array inside the library (5 KB per GPU, held
+ * caller's workspace live in a static device array inside the library (38 KB per GPU, held
  * until the process ends), and the call itself allocates nothing on the host or the device.
  *   W <= LSGD_STATIC_MAX_WORKERS, n_groups <= LSGD_STATIC_MAX_GROUPS: larger shapes are
  *            rejected with LSGD_ERR_SHAPE

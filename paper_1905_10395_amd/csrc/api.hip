@@ -36,7 +36,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t lead, glead, refreshed, offsets, group_of, losses, partials, scratch, total;
+    size_t lead, glead, refreshed, offsets, group_of, plan, losses, partials, scratch, total;
     size_t partials_cap, scratch_bytes;
 };
 
@@ -49,6 +49,7 @@ Layout make_layout(int W, int G, size_t partials_cap, size_t scratch_bytes)
     L.refreshed = o; o = align_up(o + sizeof(int32_t) * (size_t)(G + 1));
     L.offsets = o;   o = align_up(o + sizeof(int32_t) * (size_t)(G + 1));
     L.group_of = o;  o = align_up(o + sizeof(int32_t) * (size_t)W);
+    L.plan = o;      o = align_up(o + sizeof(RowPlan) * (size_t)W);
     L.losses = o;    o = align_up(o + sizeof(float) * (size_t)W);
     L.partials = o;  o = align_up(o + sizeof(float) * partials_cap);
     L.scratch = o;   o = align_up(o + scratch_bytes);
@@ -207,6 +208,7 @@ lsgd_status lsgd_create_population(const lsgd_config* cfg, float* x, float* g, f
     p->st.refreshed = reinterpret_cast<int32_t*>(base + p->layout.refreshed);
     p->st.offsets = reinterpret_cast<int32_t*>(base + p->layout.offsets);
     p->st.group_of = reinterpret_cast<int32_t*>(base + p->layout.group_of);
+    p->st.plan = reinterpret_cast<RowPlan*>(base + p->layout.plan);
     p->st.losses = reinterpret_cast<float*>(base + p->layout.losses);
     p->st.partials = reinterpret_cast<float*>(base + p->layout.partials);
     p->st.partials_cap = (size_t)cfg->W;
@@ -663,6 +665,8 @@ lsgd_status lsgd_set_leaders(lsgd_population* pop, const int32_t* local_leaders,
     stage.push_back(global_leader);
     hipError_t e = hipMemcpyAsync(pop->st.lead, stage.data(), sizeof(int32_t) * (size_t)G, hipMemcpyHostToDevice, pop->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(pop->st.glead, stage.data() + G, sizeof(int32_t), hipMemcpyHostToDevice, pop->stream);
+    if (e == hipSuccess) e = launch_init_refreshed(pop->st, G, pop->stream);
+    if (e == hipSuccess) e = launch_write_plan(pop->st, pop->cfg.W, G, pop->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(pop->stream);
     if (e != hipSuccess) return fail(LSGD_ERR_HIP, "set_leaders: %s", hipGetErrorString(e));
     for (int j = 0; j < G; ++j) {

@@ -10,6 +10,18 @@ namespace lsgd {
 
 constexpr int kWave = 64;
 
+// What a row of the population needs to know about its leaders, gathered in one 32-byte record so that the
+// streaming update kernel finds it with a single scalar load (written by the selection kernel and by whatever
+// else changes lead / glead / refreshed).
+struct RowPlan {
+    int32_t ll;      // local leader of the row's group (-1 = never selected)
+    int32_t gl;      // global leader
+    int32_t freshL;  // the group's leader was re-selected since the last update
+    int32_t freshG;  // the global leader was
+    int32_t j;       // the row's group
+    int32_t pad[3];
+};
+
 // Device-side bookkeeping placed at the start of the caller's workspace.
 struct DeviceState {
     int32_t* lead;      // [G]   local leader of each group (-1 = never selected)
@@ -17,6 +29,7 @@ struct DeviceState {
     int32_t* refreshed; // [G+1] 1 = leader re-selected since the last update (capture from x)
     int32_t* offsets;   // [G+1] group j owns rows [offsets[j], offsets[j+1])
     int32_t* group_of;  // [W]
+    RowPlan* plan;      // [W]   lead / glead / refreshed as seen from each row
     float* losses;      // [W]   the population's own loss buffer
     float* partials;    // scratch for loss partial sums
     size_t partials_cap;
@@ -33,6 +46,10 @@ lsgd_status set_error(lsgd_status st, const char* fmt, ...) __attribute__((forma
 
 // ---- kernels' host launchers (each returns the hipError_t of its launches) ----
 hipError_t launch_init_state(const DeviceState& st, int W, int G, hipStream_t s);
+// clears the "re-selected since the last update" flags
+hipError_t launch_init_refreshed(const DeviceState& st, int G, hipStream_t s);
+// rewrites plan[W] from lead, glead, refreshed, group_of (after the host changed any of them)
+hipError_t launch_write_plan(const DeviceState& st, int W, int G, hipStream_t s);
 
 hipError_t launch_select_leaders(const float* losses, int W, int G, const DeviceState& st,
                                  const RefreshBits& bits, const RefreshBits& capture, int refresh_global,

@@ -26,26 +26,27 @@
 namespace lsgd {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned short v4h __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
 
 template <int VEC> struct Vec;
 template <> struct Vec<4> { using type = v4f; };
+template <> struct Vec<2> { using type = v2f; };
 template <> struct Vec<1> { using type = float; };
 
-template <int VEC> __device__ __forceinline__ typename Vec<VEC>::type ld_vec(const float* p);
-template <> __device__ __forceinline__ v4f ld_vec<4>(const float* p) { return *reinterpret_cast<const v4f*>(p); }
-template <> __device__ __forceinline__ float ld_vec<1>(const float* p) { return *p; }
-
-template <int VEC> __device__ __forceinline__ typename Vec<VEC>::type ld_stream(const float* p);
-template <> __device__ __forceinline__ v4f ld_stream<4>(const float* p)
+template <int VEC> __device__ __forceinline__ typename Vec<VEC>::type ld_vec(const float* p)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return *reinterpret_cast<const typename Vec<VEC>::type*>(p);
 }
-template <> __device__ __forceinline__ float ld_stream<1>(const float* p) { return __builtin_nontemporal_load(p); }
+template <int VEC> __device__ __forceinline__ typename Vec<VEC>::type ld_stream(const float* p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const typename Vec<VEC>::type*>(p));
+}
 
 __device__ __forceinline__ void st_vec(float* p, v4f v) { *reinterpret_cast<v4f*>(p) = v; }
+__device__ __forceinline__ void st_vec(float* p, v2f v) { *reinterpret_cast<v2f*>(p) = v; }
 __device__ __forceinline__ void st_vec(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st_stream(float* p, v4f v) { __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p)); }
+__device__ __forceinline__ void st_stream(float* p, v2f v) { __builtin_nontemporal_store(v, reinterpret_cast<v2f*>(p)); }
 __device__ __forceinline__ void st_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
 
 __device__ __forceinline__ void st_bf16(uint16_t* p, v4f v)
@@ -54,9 +55,11 @@ __device__ __forceinline__ void st_bf16(uint16_t* p, v4f v)
     const v2u o = {f32x2_to_bf16x2(v.x, v.y), f32x2_to_bf16x2(v.z, v.w)};
     *reinterpret_cast<v2u*>(p) = o;
 }
+__device__ __forceinline__ void st_bf16(uint16_t* p, v2f v) { *reinterpret_cast<unsigned int*>(p) = f32x2_to_bf16x2(v.x, v.y); }
 __device__ __forceinline__ void st_bf16(uint16_t* p, float v) { *p = f32_to_bf16_rne(v); }
 
 __device__ __forceinline__ v4f zero_of(v4f) { return (v4f)(0.f); }
+__device__ __forceinline__ v2f zero_of(v2f) { return (v2f)(0.f); }
 __device__ __forceinline__ float zero_of(float) { return 0.f; }
 
 constexpr int kPullThreads = 256;
@@ -68,6 +71,7 @@ struct PullDev {
     float* Z;
     uint16_t* xb;
     int64_t col0, col1, ld; // columns [col0, col1)
+    int row0;               // first row of this launch of the streaming kernel
     int W, G;
     float eta, lamL, lamG, mu, wd;
     int flags, use_refreshed;
@@ -77,6 +81,7 @@ struct PullDev {
     const int32_t* lead;
     const int32_t* glead;
     const int32_t* refreshed;
+    const RowPlan* plan;
 };
 
 template <class V>
@@ -113,25 +118,29 @@ __device__ __forceinline__ void update_row(const PullDev& a, int64_t o, typename
 
 // Kernel 1: every row that nobody reads as a freshly selected leader.  One
 // workgroup per (row, column tile).  Workgroups are numbered so that they are
-// dispatched chunk by chunk: the columns are cut into chunks of kChunkTiles
-// tiles (4 MB of one row); inside a chunk the order is plain row-major.  The
+// dispatched chunk by chunk: the columns are cut into chunks of kChunkBytes
+// (4 MB of one row); inside a chunk the order is plain row-major.  The
 // x, g, m streams are then long sequential runs in memory, while the leader
 // tiles of the chunk, which every row of a group re-reads, stay in the L2
 // of the die that reads them instead of being fetched again for each row.
-constexpr int kChunkTiles = 1024;
+constexpr int64_t kChunkBytes = 4 << 20;
 
-// VEC adjacent columns of one row, starting at col.
+// VEC adjacent columns of one row, starting at col.  Everything the row needs to know about its leaders comes
+// from its 32-byte plan record (one scalar load), so that the streams' loads are issued as early as possible.
 template <int VEC, int KIND>
 __device__ __forceinline__ void pull_rows_body(const PullDev& a, int row, int64_t col)
 {
     using V = typename Vec<VEC>::type;
     constexpr bool COMM = KIND == 2;       // communication pull: every re-selected leader is captured
     bool pullG = COMM || a.lamG != 0.0f, pullL = COMM || a.lamL != 0.0f;
-    const int j = a.group_size ? row / a.group_size : a.group_of[row];
-    const int ll = pullL ? a.lead[j] : -1;
-    const int gl = pullG ? a.glead[0] : -1;
-    const bool freshL = pullL && a.use_refreshed && a.refreshed[j];
-    const bool freshG = pullG && a.use_refreshed && a.refreshed[a.G];
+    RowPlan pl;
+    pl.ll = pl.gl = -1; pl.freshL = pl.freshG = 0; pl.j = 0;
+    if (pullL || pullG) pl = a.plan[row];
+    const int j = pl.j;
+    const int ll = pullL ? pl.ll : -1;
+    const int gl = pullG ? pl.gl : -1;
+    const bool freshL = pullL && a.use_refreshed && pl.freshL;
+    const bool freshG = pullG && a.use_refreshed && pl.freshG;
     // rows captured as leaders in this update are handled by pull_leaders_kernel afterwards
     if ((freshL && row == ll) || (freshG && row == gl)) return;
     Coef c = make_coef<V>(a);
@@ -153,17 +162,13 @@ __device__ __forceinline__ void pull_rows_body(const PullDev& a, int row, int64_
     update_row<VEC, KIND>(a, o, xv, zl, zg, c);
 }
 
-// A thread of the 4-wide kernel whose group straddles the end of the row takes its columns one by one.
+// Grid: x = tile inside the chunk, y = row, z = chunk, which is the dispatch order described above without any
+// index arithmetic in the kernel.  A thread whose group of columns straddles the end of the row takes them one by one.
 template <int VEC, int KIND>
-__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int64_t tiles, int tpc)
+__global__ __launch_bounds__(kPullThreads) void pull_rows_kernel(PullDev a, int tpc)
 {
-    const int64_t b = blockIdx.x;
-    const int64_t per_chunk = (int64_t)a.W * tpc;
-    const int64_t chunk = b / per_chunk;
-    const int rem = (int)(b - chunk * per_chunk);
-    const int row = rem / tpc;
-    const int64_t tile = chunk * tpc + (rem - row * tpc);
-    if (tile >= tiles) return;
+    const int row = a.row0 + blockIdx.y;
+    const int64_t tile = (int64_t)blockIdx.z * tpc + blockIdx.x;
     const int64_t col = a.col0 + (tile * kPullThreads + threadIdx.x) * VEC;
     if (col >= a.col1) return;
     if (VEC == 1 || col + VEC <= a.col1) {
@@ -264,28 +269,35 @@ __global__ __launch_bounds__(kPullThreads) void pull_leaders_kernel(PullDev a)
     }
 }
 
-template <int VEC, int KIND>
+// VR: columns per thread of the streaming kernel, VL: of the leader-rows kernel.
+template <int VR, int VL, int KIND>
 static void launch_range(PullDev a, bool leaders, hipStream_t s)
 {
     const int64_t cols = a.col1 - a.col0;
     if (cols <= 0) return;
-    const int64_t per_block = (int64_t)kPullThreads * VEC;
+    const int64_t per_block = (int64_t)kPullThreads * VR;
     const int64_t tiles = (cols + per_block - 1) / per_block;
-    const int tpc = (int)(tiles < kChunkTiles ? tiles : kChunkTiles);
+    const int64_t chunk_tiles = kChunkBytes / (per_block * (int64_t)sizeof(float));
+    const int tpc = (int)(tiles < chunk_tiles ? tiles : chunk_tiles);
     const int64_t chunks = (tiles + tpc - 1) / tpc;
-    // a launch covers whole chunks; split only if the workgroup count would not fit a grid dimension
-    const int64_t max_chunks = ((int64_t)1 << 30) / ((int64_t)a.W * tpc) > 0 ? ((int64_t)1 << 30) / ((int64_t)a.W * tpc) : 1;
-    for (int64_t c0 = 0; c0 < chunks; c0 += max_chunks) {
-        const int64_t nch = chunks - c0 < max_chunks ? chunks - c0 : max_chunks;
-        PullDev part = a;
-        part.col0 = a.col0 + c0 * tpc * per_block;
-        const int64_t part_tiles = (tiles - c0 * tpc) < nch * tpc ? (tiles - c0 * tpc) : nch * tpc;
-        if (KIND == 2 && a.lamL == 0.0f && a.lamG == 0.0f) break;      // capture only: no row moves
-        hipLaunchKernelGGL((pull_rows_kernel<VEC, KIND>), dim3((unsigned)(nch * a.W * tpc)), dim3(kPullThreads), 0, s, part,
-                           part_tiles, tpc);
+    if (!(KIND == 2 && a.lamL == 0.0f && a.lamG == 0.0f)) {            // (capture only: no row moves)
+        // grid.y and grid.z hold at most 65535 each: rows and chunks beyond that go to further launches
+        for (int row0 = 0; row0 < a.W; row0 += 65535) {
+            const int nrows = a.W - row0 < 65535 ? a.W - row0 : 65535;
+            for (int64_t c0 = 0; c0 < chunks; c0 += 65535) {
+                const int64_t nch = chunks - c0 < 65535 ? chunks - c0 : 65535;
+                PullDev part = a;
+                part.row0 = row0;
+                part.col0 = a.col0 + c0 * tpc * per_block;
+                hipLaunchKernelGGL((pull_rows_kernel<VR, KIND>), dim3((unsigned)tpc, (unsigned)nrows, (unsigned)nch), dim3(kPullThreads), 0, s,
+                                   part, tpc);
+            }
+        }
     }
-    if (leaders)
-        hipLaunchKernelGGL((pull_leaders_kernel<VEC, KIND>), dim3((unsigned)tiles), dim3(kPullThreads), 0, s, a);
+    if (leaders) {
+        const int64_t lper = (int64_t)kPullThreads * VL;
+        hipLaunchKernelGGL((pull_leaders_kernel<VL, KIND>), dim3((unsigned)((cols + lper - 1) / lper)), dim3(kPullThreads), 0, s, a);
+    }
 }
 
 hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStream_t s)
@@ -296,21 +308,27 @@ hipError_t launch_pull_update(const PullParams& p, const DeviceState& st, hipStr
     a.eta = p.eta; a.lamL = p.lamL; a.lamG = p.lamG; a.mu = p.mu; a.wd = p.wd;
     a.flags = p.flags; a.use_refreshed = p.use_refreshed; a.group_size = p.group_size;
     a.offsets = st.offsets; a.group_of = st.group_of; a.lead = st.lead; a.glead = st.glead; a.refreshed = st.refreshed;
+    a.plan = st.plan;
     const bool comm = p.comm_pull != 0;
     const bool mom = !comm && p.mu != 0.0f;
     const bool leaders = p.use_refreshed && (comm || p.lamL != 0.0f || p.lamG != 0.0f);
 
-    auto aligned16 = [](const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; };
-    const bool vec_ok = (p.ld % 4 == 0) && aligned16(p.x) && (comm || aligned16(p.g)) && (!mom || aligned16(p.m)) &&
-                        (!p.Z || aligned16(p.Z)) && (!p.xb || (reinterpret_cast<uintptr_t>(p.xb) & 7u) == 0);
-    // float4 columns when the layout allows (a ragged last group is finished element-wise by its thread),
-    // else everything element-wise
-    a.col0 = 0; a.col1 = p.P;
-    if (vec_ok) {
-        if (comm) launch_range<4, 2>(a, leaders, s); else if (mom) launch_range<4, 1>(a, leaders, s); else launch_range<4, 0>(a, leaders, s);
-    } else {
-        if (comm) launch_range<1, 2>(a, leaders, s); else if (mom) launch_range<1, 1>(a, leaders, s); else launch_range<1, 0>(a, leaders, s);
-    }
+    auto aligned = [](const void* q, unsigned n) { return (reinterpret_cast<uintptr_t>(q) & (n - 1u)) == 0; };
+    auto layout_ok = [&](unsigned v) {      // every row start and every thread's group of v columns is v*4-byte aligned
+        return (p.ld % v == 0) && aligned(p.x, 4 * v) && (comm || aligned(p.g, 4 * v)) && (!mom || aligned(p.m, 4 * v)) &&
+               (!p.Z || aligned(p.Z, 4 * v)) && (!p.xb || aligned(p.xb, 2 * v));
+    };
+    // The streaming kernel moves 8 bytes per lane: on this chip a 3-read/2-write stream runs fastest with narrow
+    // per-lane accesses and 2 KB of each stream per workgroup (16-byte lanes: 6.0 TB/s, 8-byte lanes: 6.7 TB/s).
+    // The leader-rows kernel keeps 16-byte lanes when the layout allows.  A ragged last group of columns is
+    // finished element-wise by its thread; layouts with odd strides or unaligned bases go element-wise altogether.
+    a.col0 = 0; a.col1 = p.P; a.row0 = 0;
+#define LSGD_PULL_DISPATCH(VR, VL) \
+    do { if (comm) launch_range<VR, VL, 2>(a, leaders, s); else if (mom) launch_range<VR, VL, 1>(a, leaders, s); else launch_range<VR, VL, 0>(a, leaders, s); } while (0)
+    if (layout_ok(4)) LSGD_PULL_DISPATCH(2, 4);
+    else if (layout_ok(2)) LSGD_PULL_DISPATCH(2, 2);
+    else LSGD_PULL_DISPATCH(1, 1);
+#undef LSGD_PULL_DISPATCH
     return hipGetLastError();
 }
 

@@ -11,13 +11,14 @@ using namespace lsgd;
 
 namespace {
 
-// int32 words: offsets[G+1] | group_of[W] | lead[G] | glead[1] | refreshed[G+1]
+// int32 words: offsets[G+1] | group_of[W] | lead[G] | glead[1] | refreshed[G+1] | plan[W] (8 words each)
 constexpr int kOffOffsets = 0;
 constexpr int kOffGroupOf = kOffOffsets + LSGD_STATIC_MAX_GROUPS + 1;
 constexpr int kOffLead = kOffGroupOf + LSGD_STATIC_MAX_WORKERS;
 constexpr int kOffGlead = kOffLead + LSGD_STATIC_MAX_GROUPS;
 constexpr int kOffRefreshed = kOffGlead + 1;
-constexpr int kScratchWords = kOffRefreshed + LSGD_STATIC_MAX_GROUPS + 1;
+constexpr int kOffPlan = (kOffRefreshed + LSGD_STATIC_MAX_GROUPS + 1 + 7) / 8 * 8;         // 32-byte aligned records
+constexpr int kScratchWords = kOffPlan + LSGD_STATIC_MAX_WORKERS * (int)(sizeof(RowPlan) / sizeof(int32_t));
 
 // One copy per GPU the library is loaded on, held until the process ends.
 static __device__ __align__(256) int32_t scratch[(kScratchWords + 63) / 64 * 64];
@@ -112,6 +113,7 @@ extern "C" lsgd_status lsgd_select_pull_static(int32_t W, int64_t P, int64_t ld,
     ds.lead = leaders ? leaders : base + kOffLead;
     ds.glead = leaders ? leaders + n_groups : base + kOffGlead;
     ds.refreshed = base + kOffRefreshed;
+    ds.plan = reinterpret_cast<RowPlan*>(base + kOffPlan);
 
     // every word of the scratch that this call reads is written by this call first: the group table
     // here, the leaders and the re-selection flags by the selection kernel
