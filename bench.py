@@ -3,13 +3,18 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c4|c5]
 
-Prints ONE JSON line.  `value` is worker-steps/s (W workers x steps / seconds)
-of the whole step with every input already resident in HBM.  `roofline`
-describes the dominant kernel of the workload, timed live with events on the
-stream the library launches on; `cpu_baseline` is the CPU oracle timed on a
-bounded sample of the same workload on this host.  The line also carries the
-pull-update bandwidth stress (`pull_update_stress`) whichever workload is the
-primary one, because the metric names both quantities.
+Prints ONE JSON line.  Without --workload the primary record is the pull-update
+bandwidth stress (W=32 x P=11.7M fp32, the largest configuration and the one
+the metric's "% of peak" is quoted on) and `sub_records` holds the matrix-
+completion step and the two MLP steps; with --workload X only X runs (used
+for profiling).  Every record has `value` = worker-steps/s (W workers x steps
+/ seconds) of the whole step with every input already resident in HBM, timed
+as the median of 5 repeats of `steps` steps; `roofline` for its dominant
+kernel, timed live with events on the stream the library launches on; and
+`cpu_baseline`, the CPU oracle timed on a bounded sample of the same workload
+on this host.  `hbm_ceilings` are streams of known size measured in the same
+run (read-only, copy, and the 3-read/2-write momentum update without leader
+rows, in memory order and in the update kernel's own column-chunked order).
 """
 from __future__ import annotations
 
@@ -80,15 +85,57 @@ def _events_ms(fn, reps):
     return a.elapsed_time(b) / reps
 
 
-def _timed_steps(step_fn, steps, warmup):
+REPEATS = 5
+
+
+def _timed_steps(step_fn, steps, warmup, repeats=REPEATS):
+    """Median seconds for `steps` steps over `repeats` repeats (each bracketed by a device synchronisation),
+    after `warmup` untimed steps."""
     for t in range(warmup):
         step_fn(t)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(steps):
-        step_fn(warmup + t)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0)
+    secs = []
+    t_next = warmup
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(steps):
+            step_fn(t_next + t)
+        torch.cuda.synchronize()
+        secs.append(time.perf_counter() - t0)
+        t_next += steps
+    return float(np.median(secs))
+
+
+def _events_ms_med(fn, reps, repeats=REPEATS):
+    """Median over `repeats` of the average milliseconds per call over `reps` back-to-back calls."""
+    return float(np.median([_events_ms(fn, reps) for _ in range(repeats)]))
+
+
+def hbm_ceilings(W=32, P=11_689_512):
+    """Streams of known size on buffers of the stress shape, in memory order (lsgd_stream_probe): read-only, a
+    plain copy, and the momentum update without leader rows (3 reads, 2 writes per element); and the library's
+    own update kernel with both pull coefficients zero, which moves the same bytes as the last probe but in the
+    column-chunked order the leader tiles need."""
+    import paper_1905_10395_amd as L
+    ld = wl.padded_ld(P)
+    a = torch.empty((W, ld), device=DEV).normal_(std=0.05)
+    b = torch.empty((W, ld), device=DEV).normal_(std=0.01)
+    c = torch.zeros((W, ld), device=DEV)
+    n = float(W) * ld
+    ms_read = _events_ms_med(lambda i: L.stream_probe(L.PROBE_READ, a, b), 10)
+    ms_copy = _events_ms_med(lambda i: L.stream_probe(L.PROBE_COPY, a, c), 10)
+    c.zero_()
+    ms_upd = _events_ms_med(lambda i: L.stream_probe(L.PROBE_UPDATE, a, b, c), 10)
+    pop = L.Population(a, b, 1, m=c, P=P, momentum=0.9)
+    ms_flat = _events_ms_med(lambda i: pop.pull_update(1e-3, 0.0, 0.0), 10)
+    out = {"read_GBs": 4.0 * n / (ms_read * 1e-3) / 1e9, "copy_GBs": 8.0 * n / (ms_copy * 1e-3) / 1e9,
+           "stream_3r2w_memory_order_GBs": 20.0 * n / (ms_upd * 1e-3) / 1e9,
+           "stream_3r2w_chunked_order_GBs": 20.0 * W * P / (ms_flat * 1e-3) / 1e9,
+           "note": "measured in this run on [32, 11689536] fp32 buffers: lsgd_stream_probe (read / copy / update, memory order) and "
+                   "lsgd_pull_update(eta, 0, 0) with momentum (the update kernel's own column-chunked order)"}
+    del pop, a, b, c
+    torch.cuda.empty_cache()
+    return out
 
 
 # ------------------------------------------------------------------------------------------
@@ -121,15 +168,15 @@ def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512, copy_ref=False):
         pop.select_leaders(losses[i % 16]); pop.pull_update(eta, lamL, lamG)
     def sel(i):
         pop.select_leaders(losses[i % 16])
-    ms_both = _events_ms(upd, max(steps, 10))
-    ms_sel = _events_ms(sel, 200)
+    ms_both = _events_ms_med(upd, max(steps, 10))
+    ms_sel = _events_ms_med(sel, 200)
     ms_pull = ms_both - ms_sel
     bytes_per_launch = 20.0 * W * P
     ach = bytes_per_launch / (ms_pull * 1e-3) / 1e9
     out = {
         "workload": f"pull-update stress: W={W} x P={P} fp32 in {G} groups, momentum 0.9, select+pull only",
         "value": W * steps / secs, "unit": "worker-steps/s", "ms_per_step": secs / steps * 1e3,
-        "roofline": {"kernel": "pull_rows_kernel<4,1> + pull_leaders_kernel<4,1>", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+        "roofline": {"kernel": "pull_rows_kernel<2,1> + pull_leaders_kernel<4,1>", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": _pull_traffic(W, P),
                      "bytes_per_launch": bytes_per_launch, "ms_per_launch": ms_pull},
         "ms_select": ms_sel,
@@ -192,12 +239,12 @@ def run_c2(L, steps, warmup, data):
 
     secs = _timed_steps(step, steps, warmup)
     reps = max(20, min(steps, 200))
-    ms_grad = _events_ms(lambda i: pop.grad_loss(batches[i % K]), reps)
-    ms_sel = _events_ms(lambda i: pop.select_leaders(), reps)
+    ms_grad = _events_ms_med(lambda i: pop.grad_loss(batches[i % K]), reps)
+    ms_sel = _events_ms_med(lambda i: pop.select_leaders(), reps)
 
     def upd(i):
         pop.select_leaders(); pop.pull_update(eta, lamL, lamG)
-    ms_pull = _events_ms(upd, reps) - ms_sel
+    ms_pull = _events_ms_med(upd, reps) - ms_sel
     # algorithmic bytes of the gradient stage per launch: read x and write g once (2*4P per worker)
     # plus 16 B of index + entry per batch element
     grad_bytes = W * (2 * 4.0 * prob.P + 16.0 * B)
@@ -212,7 +259,7 @@ def run_c2(L, steps, warmup, data):
         pop.step_alg1(batches[t % K], eta, gamL, gamG, lamL, lamG, (L.COMM_LOCAL | L.COMM_GLOBAL) if t % tau == 0 else 0)
     secs_alg1 = _timed_steps(step_alg1, steps, warmup)
     center = torch.empty(ld, device=DEV)
-    ms_center = _events_ms(lambda i: pop.center(center), reps)
+    ms_center = _events_ms_med(lambda i: pop.center(center), reps)
     out = {
         "workload": f"matrix completion LSGD: 20000x20000 rank 32, 1% observed ({prob.n_obs}), W={W} in {G} groups, "
                     f"B={B}/worker/step, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps",
@@ -222,11 +269,12 @@ def run_c2(L, steps, warmup, data):
                      "traffic": _traffic(MC_TRAFFIC, (W, B, prob.m, prob.n, prob.r)),
                      "bytes_per_launch": grad_bytes, "ms_per_launch": ms_grad},
         "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull},
-        "pull_update_GBs": W * 12.0 * prob.P / (ms_pull * 1e-3) / 1e9,
+        "pull_update_GBs_cache_assisted": W * 12.0 * prob.P / (ms_pull * 1e-3) / 1e9,
+        "cache_note": "x and g of this workload (164 MB) fit the 256 MB memory-side cache: the stage rates here are not HBM bandwidth",
         "final_mean_loss": float(np.mean(lossv)),
         "alg1_schedule": {"value": W * steps / secs_alg1, "unit": "worker-steps/s", "ms_per_step": secs_alg1 / steps * 1e3,
                           "comm_every": tau},
-        "center": {"ms": ms_center, "GBs": 4.0 * (W + 1) * prob.P / (ms_center * 1e-3) / 1e9},
+        "center": {"ms": ms_center, "GBs_cache_assisted": 4.0 * (W + 1) * prob.P / (ms_center * 1e-3) / 1e9},
     }
     del pop
     return out
@@ -279,7 +327,7 @@ def make_mlp(cfg):
     return P, ld, x0, batches
 
 
-def run_mlp(L, steps, warmup, cfg, data, fused=True):
+def run_mlp(L, steps, warmup, cfg, data, fused=True, measured_bw_gbs=None):
     dims, W, G, B, K, tau = cfg["dims"], cfg["W"], cfg["G"], cfg["B"], cfg["K"], cfg["tau"]
     P, ld, x0, host_batches = data
     x = torch.from_numpy(x0).to(DEV)
@@ -300,12 +348,12 @@ def run_mlp(L, steps, warmup, cfg, data, fused=True):
 
     secs = _timed_steps(step, steps, warmup)
     reps = max(10, min(steps, 100))
-    ms_grad = _events_ms(lambda i: pop.grad_loss(batches[i % K]), reps)
-    ms_sel = _events_ms(lambda i: pop.select_leaders(), reps)
+    ms_grad = _events_ms_med(lambda i: pop.grad_loss(batches[i % K]), reps)
+    ms_sel = _events_ms_med(lambda i: pop.select_leaders(), reps)
 
     def upd(i):
         pop.select_leaders(); pop.pull_update(eta, lamL, lamG)
-    ms_pull = _events_ms(upd, reps) - ms_sel
+    ms_pull = _events_ms_med(upd, reps) - ms_sel
     flops = float(W) * mlp_flops(dims, B)
     tf = flops / (ms_grad * 1e-3) / 1e12
     # traffic the gradient stage cannot avoid: read the bf16 weights once per product that uses them
@@ -327,6 +375,21 @@ def run_mlp(L, steps, warmup, cfg, data, fused=True):
                 "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None,
                 "flops_per_launch": flops, "ms_per_launch": ms_grad,
                 "hbm_floor_ms": min_bytes / (HBM_PEAK_GBS * 1e9) * 1e3}
+    # the gradient stage as a contraction: fraction of the bf16 matrix-core peak, and of what its arithmetic
+    # intensity allows (flops per byte of unavoidable traffic x memory bandwidth, datasheet and measured)
+    intensity = flops / min_bytes
+    grad_stage = {"kernel": "lsgd_grad_loss (MLP): gemm_bf16_kernel launches + narrow-layer kernels", "bound": "mfma", "achieved": tf,
+                  "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "flops_per_launch": flops, "ms_per_launch": ms_grad,
+                  "min_bytes_per_launch": min_bytes, "intensity_flop_per_byte": intensity,
+                  "intensity_roofline_TFLOPs": min(2500.0, intensity * HBM_PEAK_GBS / 1e3),
+                  "frac_of_intensity_roofline": tf / min(2500.0, intensity * HBM_PEAK_GBS / 1e3),
+                  "hbm_floor_ms": min_bytes / (HBM_PEAK_GBS * 1e9) * 1e3}
+    if measured_bw_gbs:
+        lim = min(2500.0, intensity * measured_bw_gbs / 1e3)
+        grad_stage["intensity_roofline_measured_bw_TFLOPs"] = lim
+        grad_stage["frac_of_intensity_roofline_measured_bw"] = tf / lim
+        if fused:
+            roof["frac_of_measured_copy_bw"] = roof["achieved"] / measured_bw_gbs
     out = {
         "workload": f"{cfg['name']}, synthetic 10-class Gaussian mixture, W={W} in {G} groups, batch {B}/worker, bf16 operands / "
                     f"fp32 master, momentum 0.9, eta={eta}, lam_L={lamL}, lam_G={lamG}, leaders every {tau} steps"
@@ -336,7 +399,7 @@ def run_mlp(L, steps, warmup, cfg, data, fused=True):
         "roofline": roof,
         "stage_ms": {"grad_loss": ms_grad, "select_leaders": ms_sel, "pull_update": ms_pull,
                      "note": "separate calls (gradient through memory); the timed step " + ("fuses them" if fused else "is their sum")},
-        "grad_loss_TFLOPs": tf,
+        "grad_stage_roofline": grad_stage,
         "pull_update_GBs": W * 22.0 * P / (ms_pull * 1e-3) / 1e9,
         "final_mean_loss": float(np.mean(pop.get_losses())),
     }
@@ -361,18 +424,28 @@ def cpu_mlp(cfg, data, workers, batch_frac=1.0):
         reps += 1
     dt = (time.perf_counter() - t0) / reps
     what = f"full batch {B}" if Bs == B else f"{Bs} of the {B} samples of each batch (rate scaled by {Bs}/{B})"
-    return {"value": Ws / dt * (Bs / B), "unit": "worker-steps/s", "cores": min(Ws, _omp_threads() or os.cpu_count()), "kind": "oracle",
+    return {"value": Ws / dt * (Bs / B), "unit": "worker-steps/s", "cores": _omp_threads() or os.cpu_count(), "kind": "oracle",
             "sample": f"{Ws} of the {W} workers (one group), {what}, full model, {reps} whole steps"}
+
+
+def _record(primary, cpu):
+    rec = {"value": primary["value"], "unit": primary["unit"], "ms_per_step": primary["ms_per_step"],
+           "config": {"workload": primary["workload"]}, "roofline": primary["roofline"], "cpu_baseline": cpu}
+    for k in ("stage_ms", "pull_update_GBs", "pull_update_GBs_cache_assisted", "cache_note", "final_mean_loss", "ms_select",
+              "alg1_schedule", "center", "grad_stage_roofline"):
+        if k in primary:
+            rec[k] = primary[k]
+    return rec
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c4", "c5"])
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--no-stress", action="store_true", help="skip the extra pull-update stress measurement")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="all", choices=["all", "c2", "c3", "c4", "c5"],
+                    help="all: the stress as primary record plus c2, c3, c5 as sub-records; else that workload alone")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline legs")
     ap.add_argument("--no-fuse", action="store_true", help="MLP workloads: three-call step instead of the fused update")
     ap.add_argument("--copy-ref", action="store_true", help="also run a plain device copy of one [W,ld] buffer (counter calibration)")
     args = ap.parse_args()
@@ -386,34 +459,39 @@ def main():
     import paper_1905_10395_amd as L
     L.lib()
 
-    stress = None
-    if args.workload == "c4" or not args.no_stress:
-        stress = run_stress(L, min(args.steps, 100), min(args.warmup, 10), copy_ref=args.copy_ref)
-    line = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
-    if args.workload == "c4":
-        primary = stress
-        cpu = None if args.no_cpu else cpu_stress()
-    elif args.workload in MLP_CFG:
-        cfg = MLP_CFG[args.workload]
-        data = make_mlp(cfg)
-        line["dtype"] = "bf16"
-        primary = run_mlp(L, args.steps, args.warmup, cfg, data, fused=not args.no_fuse)
-        cpu = None if args.no_cpu else (cpu_mlp(cfg, data, cfg["W"]) if args.workload == "c3" else cpu_mlp(cfg, data, 4, 0.25))
-    else:
-        data = make_c2()
-        primary = run_c2(L, args.steps, args.warmup, data)
-        cpu = None if args.no_cpu else cpu_c2(data)
-    line.update({"value": primary["value"], "unit": primary["unit"], "ms_per_step": primary["ms_per_step"],
-                 "config": {"workload": primary["workload"]}, "roofline": primary["roofline"],
-                 "cpu_baseline": cpu})
-    for k in ("stage_ms", "pull_update_GBs", "final_mean_loss", "ms_select", "alg1_schedule", "center", "grad_loss_TFLOPs"):
-        if k in primary:
-            line[k] = primary[k]
-    if stress is not None:
-        line["pull_update_stress"] = {k: stress[k] for k in ("workload", "value", "unit", "ms_per_step", "roofline")}
-    if args.workload == "c4":
-        line["steps"] = min(args.steps, 100); line["warmup"] = min(args.warmup, 10)
+    line = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "repeats": REPEATS,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
+    which = ["c4", "c2", "c3", "c5"] if args.workload == "all" else [args.workload]
+    ceil = hbm_ceilings() if args.workload in ("all", "c4") else None
+    records = {}
+    for w in which:
+        if w == "c4":
+            prim = run_stress(L, args.steps, args.warmup, copy_ref=args.copy_ref)
+            if ceil:
+                prim["roofline"]["frac_of_measured_3r2w_stream_memory_order"] = prim["roofline"]["achieved"] / ceil["stream_3r2w_memory_order_GBs"]
+                prim["roofline"]["frac_of_measured_3r2w_stream_chunked_order"] = prim["roofline"]["achieved"] / ceil["stream_3r2w_chunked_order_GBs"]
+            cpu = None if args.no_cpu else cpu_stress()
+        elif w == "c2":
+            data = make_c2()
+            prim = run_c2(L, args.steps, args.warmup, data)
+            cpu = None if args.no_cpu else cpu_c2(data)
+            del data
+        else:
+            cfg = MLP_CFG[w]
+            data = make_mlp(cfg)
+            prim = run_mlp(L, args.steps, args.warmup, cfg, data, fused=not args.no_fuse,
+                           measured_bw_gbs=ceil["copy_GBs"] if ceil else None)
+            cpu = None if args.no_cpu else (cpu_mlp(cfg, data, cfg["W"]) if w == "c3" else cpu_mlp(cfg, data, 2, 0.25))
+            del data
+        records[w] = _record(prim, cpu)
+        records[w]["dtype"] = "f32" if w in ("c2", "c4") else "bf16"
+        torch.cuda.empty_cache()
+    first = which[0]
+    line.update(records[first])
+    if ceil:
+        line["hbm_ceilings"] = ceil
+    if len(which) > 1:
+        line["sub_records"] = {w: records[w] for w in which[1:]}
     print(json.dumps(line))
 
 

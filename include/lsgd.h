@@ -315,6 +315,17 @@ lsgd_status lsgd_select_pull_static(int32_t W, int64_t P, int64_t ld, int32_t n_
                                     float lambda_G, float momentum, float weight_decay, int32_t flags,
                                     void* hip_stream);
 
+/* Measurement aid, not part of the method: one pass of a plain stream over n floats per buffer, in
+ * memory order, so that a benchmark can report what the memory system at hand gives the access
+ * shapes the update uses, beside the update's own rate.
+ *   LSGD_PROBE_READ    reads a                              (4 n bytes)
+ *   LSGD_PROBE_COPY    b <- a                               (8 n bytes)
+ *   LSGD_PROBE_UPDATE  c <- 0.9 c + b ; a <- a - 1e-3 c     (20 n bytes: the momentum update without
+ *                      leader rows, 3 reads and 2 writes per element)
+ * a, b, c: device [n] fp32, 8-byte aligned, n even (c may be NULL except for LSGD_PROBE_UPDATE).     */
+enum { LSGD_PROBE_READ = 0, LSGD_PROBE_COPY = 1, LSGD_PROBE_UPDATE = 2 };
+lsgd_status lsgd_stream_probe(int32_t kind, float* a, float* b, float* c, int64_t n, void* hip_stream);
+
 /* Message for the last failing call on this thread ("" if none).  Static storage. */
 const char* lsgd_last_error(void);
 

@@ -94,6 +94,7 @@ def lib():
         L.lsgd_select_pull_static.argtypes = [C.c_int32, C.c_int64, C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float,
                                               C.c_float, C.c_float, C.c_float, C.c_int32, C.c_void_p]
+        L.lsgd_stream_probe.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
         L.lsgd_get_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.lsgd_get_losses.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
         L.lsgd_set_leaders.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
@@ -170,6 +171,16 @@ def workspace_bytes(W, P, ld, n_groups, group_offsets=None, momentum=0.0, flags=
     if n == 0:
         raise LsgdError(-1, lib().lsgd_last_error().decode())
     return n
+
+
+PROBE_READ, PROBE_COPY, PROBE_UPDATE = 0, 1, 2
+
+
+def stream_probe(kind, a, b, c=None, stream=None):
+    """lsgd_stream_probe over the whole of the (contiguous, equally sized) float32 tensors a, b, c."""
+    assert a.is_contiguous() and b.is_contiguous() and a.numel() == b.numel() and (c is None or c.numel() == a.numel())
+    st = torch.cuda.current_stream(a.device) if stream is None else stream
+    _check(lib().lsgd_stream_probe(int(kind), _ptr(a), _ptr(b), _ptr(c), a.numel(), C.c_void_p(st.cuda_stream)))
 
 
 STATIC_MAX_WORKERS, STATIC_MAX_GROUPS = 1024, 64
