@@ -35,7 +35,7 @@ import workloads as wl
 # Bytes between the L2 caches and memory per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by
 # reference kernels of known size (profiles/*_hbm_traffic.md).  Valid only for the kernel source they were
 # taken on: reported as null once that file's code (comments and white space aside) differs.
-PULL_TRAFFIC = {"file": "pull_update.hip", "code_sha256_16": "c1af6e928c94a4f6", "bytes_per_launch": 7.668e9,
+PULL_TRAFFIC = {"file": "pull_update.hip", "code_sha256_16": "ce89fd10d8336956", "bytes_per_launch": 7.666e9,
                 "key": (32, 11_689_512)}
 MC_TRAFFIC = {"file": "mc_grad.hip", "code_sha256_16": "b7100f28d40b05f7", "bytes_per_launch": 3.935e8,
               "key": (16, 65536, 20000, 20000, 32)}
@@ -152,10 +152,10 @@ def run_stress(L, steps, warmup, W=32, G=4, P=11_689_512, copy_ref=False):
     pop = L.Population(x, g, G, m=m, P=P, momentum=0.9)
     eta, lamL, lamG = 0.01, 0.1, 0.05
     if copy_ref:
-        # a plain copy of known size (reads and writes W*ld*4 bytes each), the reference that scales
-        # the FETCH_SIZE / WRITE_SIZE counters of a profiled run
+        # a plain copy of known size (lsgd_stream_probe: reads W*ld*4 bytes, writes W*ld*4 bytes), the
+        # reference that scales the FETCH_SIZE / WRITE_SIZE counters of a profiled run
         for _ in range(3):
-            m.copy_(g)
+            L.stream_probe(L.PROBE_COPY, g, m)
         m.zero_()
 
     def step(t):
@@ -448,6 +448,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline legs")
     ap.add_argument("--no-fuse", action="store_true", help="MLP workloads: three-call step instead of the fused update")
     ap.add_argument("--copy-ref", action="store_true", help="also run a plain device copy of one [W,ld] buffer (counter calibration)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the stream-ceiling measurements (profiling runs of the update alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; every population lives on a single device "
@@ -462,7 +463,7 @@ def main():
     line = {"metric": METRIC, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "repeats": REPEATS,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic"}
     which = ["c4", "c2", "c3", "c5"] if args.workload == "all" else [args.workload]
-    ceil = hbm_ceilings() if args.workload in ("all", "c4") else None
+    ceil = hbm_ceilings() if args.workload in ("all", "c4") and not args.no_ceilings else None
     records = {}
     for w in which:
         if w == "c4":
