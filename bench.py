@@ -138,6 +138,19 @@ def hbm_ceilings(W=32, P=11_689_512):
     return out
 
 
+def mfma_ceiling(n=8192, reps=10):
+    """What the vendor library's plain bf16 GEMM reaches on this machine at n^3 (context for the MLP kernels' matrix-core
+    figures: the datasheet's 2.5 PFLOP/s is not what a real GEMM sustains)."""
+    a = torch.randn((n, n), device=DEV, dtype=torch.bfloat16)
+    b = torch.randn((n, n), device=DEV, dtype=torch.bfloat16)
+    c = torch.empty((n, n), device=DEV, dtype=torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a, b, out=c)
+    ms = _events_ms_med(lambda i: torch.matmul(a, b, out=c), reps)
+    return {"vendor_gemm_bf16_TFLOPs": 2.0 * n ** 3 / (ms * 1e-3) / 1e12, "shape": f"{n}x{n}x{n}",
+            "note": "torch.matmul (vendor library) bf16 with fp32 accumulation, measured in this run; peak used for fractions stays 2500"}
+
+
 # ------------------------------------------------------------------------------------------
 # C4: pull-update bandwidth stress (leader selection + fused pull/momentum update only)
 # ------------------------------------------------------------------------------------------
@@ -491,6 +504,8 @@ def main():
     line.update(records[first])
     if ceil:
         line["hbm_ceilings"] = ceil
+    if any(w in MLP_CFG for w in which):
+        line["mfma_ceiling"] = mfma_ceiling()
     if len(which) > 1:
         line["sub_records"] = {w: records[w] for w in which[1:]}
     print(json.dumps(line))
