@@ -167,6 +167,23 @@ lsgd_status lsgd_destroy_population(lsgd_population* pop);
  * `losses` is NULL, otherwise into `losses`.                                   */
 lsgd_status lsgd_grad_loss(lsgd_population* pop, const lsgd_batch* batch, float* losses);
 
+/* Objective values only: losses[i] = f_i(x_i) on worker i's part of the batch at
+ * the current parameters (device [W]; NULL = the population's own loss buffer);
+ * g is neither read nor written.  This is what choosing a leader costs (Section
+ * 3.1.3: the leader is the worker whose estimate of the objective, one draw per
+ * worker, is smallest; Algorithm 1 determines the best workers after the local
+ * step, at the parameters that step produced, on the sample of the iteration
+ * that follows).  lsgd_step and
+ * lsgd_step_alg1 select from the losses of their own gradient pass, i.e. at the
+ * parameters before the step; the printed order is
+ *   lsgd_step_alg1(..., comm = 0); lsgd_loss(next batch, NULL);
+ *   lsgd_select_leaders(NULL, mask, global); lsgd_leader_pull(lambda, lambda_G).
+ * Same batch kinds, checks and workspace as lsgd_grad_loss.  For LSGD_BATCH_MC
+ * the squared residuals are summed in another order than in lsgd_grad_loss, so
+ * the two values can differ in the last bits; for LSGD_BATCH_MLP it is the
+ * forward pass of lsgd_grad_loss (bit-identical losses).                        */
+lsgd_status lsgd_loss(lsgd_population* pop, const lsgd_batch* batch, float* losses);
+
 /* Segmented argmin.  For each group j with refresh_local[j] != 0 (host
  * [n_groups]; NULL = all) the local leader becomes the lowest index attaining the
  * group's minimum loss; if refresh_global the global leader becomes the lowest

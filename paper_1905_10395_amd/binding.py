@@ -245,6 +245,9 @@ class Population:
     def grad_loss(self, batch, losses=None):
         _check(lib().lsgd_grad_loss(self._h, C.byref(batch.c), _ptr(losses)))
 
+    def loss(self, batch, losses=None):
+        _check(lib().lsgd_loss(self._h, C.byref(batch.c), _ptr(losses)))
+
     def select_leaders(self, losses=None, refresh_local=None, refresh_global=1):
         _check(lib().lsgd_select_leaders(self._h, _ptr(losses), self._mask(refresh_local), int(refresh_global)))
 

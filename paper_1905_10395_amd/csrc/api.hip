@@ -289,6 +289,42 @@ lsgd_status do_grad_loss(lsgd_population* p, const lsgd_batch* batch, float* los
     return LSGD_OK;
 }
 
+// objective values only, at the current parameters; g is left alone
+lsgd_status do_loss(lsgd_population* p, const lsgd_batch* batch, float* losses_out)
+{
+    float* losses = losses_out ? losses_out : p->st.losses;
+    hipError_t e = hipSuccess;
+    switch (batch->kind) {
+    case LSGD_BATCH_EXTERNAL: {
+        const auto* d = static_cast<const lsgd_external_batch*>(batch->desc);
+        if (d->losses != losses)
+            e = hipMemcpyAsync(losses, d->losses, sizeof(float) * (size_t)p->cfg.W, hipMemcpyDeviceToDevice, p->stream);
+        break;
+    }
+    case LSGD_BATCH_MC: {
+        const auto* d = static_cast<const lsgd_mc_batch*>(batch->desc);
+        DeviceState st = p->st;
+        if (mc_partials(p->cfg.W, *d) > (size_t)p->cfg.W) st.partials = reinterpret_cast<float*>(p->st.scratch);
+        e = launch_mc_loss(p->x, losses, p->cfg.W, p->cfg.ld, *d, st, p->stream);
+        break;
+    }
+    case LSGD_BATCH_MLP: {
+        const auto* d = static_cast<const lsgd_mlp_batch*>(batch->desc);
+        if (!p->shadow_valid) {
+            e = launch_cast_shadow(p->x, p->xb, p->cfg.W, p->cfg.P, p->cfg.ld, p->stream);
+            if (e != hipSuccess) break;
+            p->shadow_valid = true;
+        }
+        e = launch_mlp_forward(p->xb, p->x, losses, p->cfg.W, p->cfg.P, p->cfg.ld, *d, p->st, p->stream);
+        break;
+    }
+    default: break;
+    }
+    if (e != hipSuccess) return fail(LSGD_ERR_HIP, "loss: %s", hipGetErrorString(e));
+    if (!losses_out) p->losses_valid = true;
+    return LSGD_OK;
+}
+
 lsgd_status check_grad_loss(lsgd_population* p, const lsgd_batch* batch)
 {
     size_t partials = 0, scratch = 0;
@@ -458,6 +494,14 @@ lsgd_status lsgd_grad_loss(lsgd_population* pop, const lsgd_batch* batch, float*
     lsgd_status st = check_grad_loss(pop, batch);
     if (st != LSGD_OK) return st;
     return do_grad_loss(pop, batch, losses);
+}
+
+lsgd_status lsgd_loss(lsgd_population* pop, const lsgd_batch* batch, float* losses)
+{
+    if (!pop) return fail(LSGD_ERR_INVALID_ARG, "population is NULL");
+    lsgd_status st = check_grad_loss(pop, batch);
+    if (st != LSGD_OK) return st;
+    return do_loss(pop, batch, losses);
 }
 
 lsgd_status lsgd_select_leaders(lsgd_population* pop, const float* losses, const uint8_t* refresh_local, int refresh_global)

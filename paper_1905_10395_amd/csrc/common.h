@@ -82,6 +82,9 @@ size_t mc_scratch_bytes(int W, const lsgd_mc_batch& b);
 size_t mc_partials(int W, const lsgd_mc_batch& b);
 hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, int64_t P, int64_t ld,
                                const lsgd_mc_batch& b, const DeviceState& st, hipStream_t s);
+// objective values only (no gradient); needs the same loss-partial slots as launch_mc_grad_loss
+hipError_t launch_mc_loss(const float* x, float* losses, int W, int64_t ld, const lsgd_mc_batch& b, const DeviceState& st,
+                          hipStream_t s);
 
 hipError_t launch_mc_pack(const int32_t* rows, const int32_t* cols, const float* vals, int64_t n, lsgd_mc_entry* out, hipStream_t s);
 

@@ -45,8 +45,9 @@ __device__ __forceinline__ void fetch_entry(const lsgd_mc_entry* __restrict__ en
 
 // General path: S lanes cooperate on one entry (S = power of two >= min(r, 64)),
 // residual by a lane butterfly, gradient rows accumulated with hardware fp32
-// atomics into the zero-filled g.  Any r, m, n.
-template <int S>
+// atomics into the zero-filled g.  Any r, m, n.  GRAD = false evaluates the
+// squared residuals only (g may be NULL).
+template <int S, bool GRAD>
 __global__ __launch_bounds__(kMcThreads) void mc_grad_atomic_kernel(
     const float* __restrict__ x, float* __restrict__ g, int64_t ld, int m, int n, int r,
     const int32_t* __restrict__ rows, const int32_t* __restrict__ cols, const float* __restrict__ vals,
@@ -56,8 +57,8 @@ __global__ __launch_bounds__(kMcThreads) void mc_grad_atomic_kernel(
     const int w = blockIdx.y;
     const float* U = x + (int64_t)w * ld;
     const float* V = U + (int64_t)m * r;
-    float* gU = g + (int64_t)w * ld;
-    float* gV = gU + (int64_t)m * r;
+    float* gU = GRAD ? g + (int64_t)w * ld : nullptr;
+    float* gV = GRAD ? gU + (int64_t)m * r : nullptr;
     const int sub = threadIdx.x / S, q0 = threadIdx.x % S;
     constexpr int kSubs = kMcThreads / S;
     const int64_t k0 = (int64_t)blockIdx.x * kMcEntriesPerBlock;
@@ -76,10 +77,12 @@ __global__ __launch_bounds__(kMcThreads) void mc_grad_atomic_kernel(
         for (int d = 1; d < S; d <<= 1) dot += __shfl_xor(dot, d, S);
         const float e = dot - mv;
         if (q0 == 0) sq = fmaf(e, e, sq);
-        const float f = two_c * e;
-        for (int q = q0; q < r; q += S) {
-            unsafeAtomicAdd(gU + (int64_t)a * r + q, f * vb[q]);
-            unsafeAtomicAdd(gV + (int64_t)b * r + q, f * ua[q]);
+        if (GRAD) {
+            const float f = two_c * e;
+            for (int q = q0; q < r; q += S) {
+                unsafeAtomicAdd(gU + (int64_t)a * r + q, f * vb[q]);
+                unsafeAtomicAdd(gV + (int64_t)b * r + q, f * ua[q]);
+            }
         }
     }
     // block sum of squared residuals in a fixed order
@@ -563,9 +566,34 @@ hipError_t launch_mc_grad_loss(const float* x, float* g, float* losses, int W, i
     if (nblk > 0) {
         dim3 grid((unsigned)nblk, (unsigned)W);
         const float two_c = 2.0f * b.c;
-#define LSGD_MC_LAUNCH(S)                                                                                     \
-    hipLaunchKernelGGL((mc_grad_atomic_kernel<S>), grid, dim3(kMcThreads), 0, s, x, g, ld, b.m, b.n, b.r,     \
+#define LSGD_MC_LAUNCH(S)                                                                                       \
+    hipLaunchKernelGGL((mc_grad_atomic_kernel<S, true>), grid, dim3(kMcThreads), 0, s, x, g, ld, b.m, b.n, b.r, \
                        b.rows, b.cols, b.vals, b.batch_idx, nb, two_c, st.partials, nblk, b.entries)
+        if (b.r <= 1) LSGD_MC_LAUNCH(1);
+        else if (b.r <= 2) LSGD_MC_LAUNCH(2);
+        else if (b.r <= 4) LSGD_MC_LAUNCH(4);
+        else if (b.r <= 8) LSGD_MC_LAUNCH(8);
+        else if (b.r <= 16) LSGD_MC_LAUNCH(16);
+        else if (b.r <= 32) LSGD_MC_LAUNCH(32);
+        else LSGD_MC_LAUNCH(64);
+#undef LSGD_MC_LAUNCH
+    }
+    hipLaunchKernelGGL(mc_loss_finish_kernel, dim3((unsigned)W), dim3(256), 0, s, st.partials, nblk, b.c, losses);
+    return hipGetLastError();
+}
+
+// Objective values only: the residual pass of the general path without its atomics, one partial sum per
+// block of entries, then the same fixed-order finish.
+hipError_t launch_mc_loss(const float* x, float* losses, int W, int64_t ld, const lsgd_mc_batch& b, const DeviceState& st,
+                          hipStream_t s)
+{
+    const int64_t nb = mc_entries(b);
+    const int nblk = (int)((nb + kMcEntriesPerBlock - 1) / kMcEntriesPerBlock);
+    if (nblk > 0) {
+        dim3 grid((unsigned)nblk, (unsigned)W);
+#define LSGD_MC_LAUNCH(S)                                                                                              \
+    hipLaunchKernelGGL((mc_grad_atomic_kernel<S, false>), grid, dim3(kMcThreads), 0, s, x, (float*)nullptr, ld, b.m, b.n, \
+                       b.r, b.rows, b.cols, b.vals, b.batch_idx, nb, 0.0f, st.partials, nblk, b.entries)
         if (b.r <= 1) LSGD_MC_LAUNCH(1);
         else if (b.r <= 2) LSGD_MC_LAUNCH(2);
         else if (b.r <= 4) LSGD_MC_LAUNCH(4);

@@ -681,6 +681,36 @@ __global__ __launch_bounds__(256) void fwd_narrow_kernel(const uint16_t* __restr
     }
 }
 
+// db[o] = sum_b deltaT[o][b] with 16-byte loads, half a wavefront per o.  B % 8 == 0, rows 16-byte aligned.
+__global__ __launch_bounds__(256) void db_vec_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, int B, int dout, float* __restrict__ g,
+                                                     int64_t sG, FusedUpdate fu, int64_t col0)
+{
+    const int lane = threadIdx.x & 63, l = lane & 31;
+    const int o = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 2 + (lane >> 5);
+    const int w = blockIdx.y;
+    float acc = 0.f;
+    if (o < dout) {
+        const u32x4* dt = reinterpret_cast<const u32x4*>(deltaT + (int64_t)w * sD + (int64_t)o * B);
+        for (int c = l; c < B / 8; c += 32) {
+            float a[8];
+            unpack8(dt[c], a);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) acc += a[t];
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 32; d <<= 1) acc += __shfl_xor(acc, d, 64);
+    if (l == 0 && o < dout) {
+        if (fu.enabled) {
+            const int off[1] = {0};
+            const float gv[1] = {acc};
+            fused_apply<1>(fused_row(fu, w, sG), col0 + o, off, gv);
+        } else {
+            g[(int64_t)w * sG + o] = acc;
+        }
+    }
+}
+
 // dW[o][i..i+7] for one output row o and 512 columns per workgroup; the four wavefronts split the batch
 // and combine through LDS in a fixed order.  d_in % 8 == 0.
 __global__ __launch_bounds__(256) void dw_narrow_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, const uint16_t* __restrict__ H,
@@ -978,8 +1008,15 @@ hipError_t launch_mlp_backward(const uint16_t* xb, const float* x, float* g, int
             }
         }
         // db_k
-        hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, sc16 + p.dT[k], sW16, B, dout,
-                           g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
+        {
+            const uint16_t* dTk = sc16 + p.dT[k];
+            if (B % 8 == 0 && sW16 % 8 == 0 && (reinterpret_cast<uintptr_t>(dTk) & 15u) == 0)
+                hipLaunchKernelGGL(db_vec_kernel, dim3((unsigned)((dout + 7) / 8), (unsigned)W), dim3(256), 0, s, dTk, sW16, B, dout,
+                                   g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
+            else
+                hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, dTk, sW16, B, dout,
+                                   g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
+        }
     }
     if (fused) return hipGetLastError();          // g is not written, so there is no padding to clear
     if (ld > P)
