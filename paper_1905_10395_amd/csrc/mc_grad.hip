@@ -96,6 +96,65 @@ __global__ __launch_bounds__(kMcThreads) void mc_grad_atomic_kernel(
     if (threadIdx.x == 0) partials[(int64_t)w * nblk + blockIdx.x] = red[0];
 }
 
+// Objective only, rank a multiple of 4 and 16-byte aligned rows: LPE lanes share an entry with one float4
+// of each factor row per lane, and four entries per lane group are in flight (index, record and both rows
+// of each are fetched before the first product), since nothing but gathers happens here.
+template <int LPE>
+__global__ __launch_bounds__(kMcThreads) void mc_loss_vec_kernel(
+    const float* __restrict__ x, int64_t ld, int m, int n, int r,
+    const int32_t* __restrict__ rows, const int32_t* __restrict__ cols, const float* __restrict__ vals,
+    const int32_t* __restrict__ batch_idx, int64_t nb, float* __restrict__ partials, int nblk,
+    const lsgd_mc_entry* __restrict__ entries)
+{
+    constexpr int kSubs = kMcThreads / LPE, kFly = 4;
+    const int w = blockIdx.y;
+    const float* U = x + (int64_t)w * ld;
+    const float* V = U + (int64_t)m * r;
+    const int sub = threadIdx.x / LPE, q0 = threadIdx.x % LPE;
+    const bool lane_on = q0 < (r >> 2);
+    const int64_t k0 = (int64_t)blockIdx.x * kMcEntriesPerBlock;
+    const int64_t k1 = (k0 + kMcEntriesPerBlock < nb) ? k0 + kMcEntriesPerBlock : nb;
+    float sq = 0.f;
+    for (int64_t kb = k0; kb < k1; kb += kSubs * kFly) {
+        float4 ua[kFly], vb[kFly];
+        float mv[kFly];
+        bool live[kFly];
+#pragma unroll
+        for (int u = 0; u < kFly; ++u) {
+            const int64_t k = kb + (int64_t)u * kSubs + sub;
+            live[u] = k < k1;
+            const int64_t kc = live[u] ? k : k1 - 1;           // a lane group past the end repeats the last entry
+            const int64_t s = batch_idx ? (int64_t)batch_idx[(int64_t)w * nb + kc] : kc;
+            int a, b;
+            fetch_entry(entries, rows, cols, vals, s, a, b, mv[u]);
+            ua[u] = vb[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (lane_on) {
+                ua[u] = reinterpret_cast<const float4*>(U + (int64_t)a * r)[q0];
+                vb[u] = reinterpret_cast<const float4*>(V + (int64_t)b * r)[q0];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kFly; ++u) {
+            float dot = ua[u].x * vb[u].x;
+            dot = fmaf(ua[u].y, vb[u].y, dot);
+            dot = fmaf(ua[u].z, vb[u].z, dot);
+            dot = fmaf(ua[u].w, vb[u].w, dot);
+#pragma unroll
+            for (int d = 1; d < LPE; d <<= 1) dot += __shfl_xor(dot, d, LPE);
+            const float e = dot - mv[u];
+            if (q0 == 0 && live[u]) sq = fmaf(e, e, sq);
+        }
+    }
+    __shared__ float red[kMcThreads];
+    red[threadIdx.x] = sq;
+    __syncthreads();
+    for (int d = kMcThreads / 2; d > 0; d >>= 1) {
+        if (threadIdx.x < d) red[threadIdx.x] += red[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partials[(int64_t)w * nblk + blockIdx.x] = red[0];
+}
+
 // losses[w] = c * sum of the worker's partial sums, accumulated in fp64 in a fixed order.
 __global__ __launch_bounds__(256) void mc_loss_finish_kernel(const float* __restrict__ partials, int nblk, float c,
                                                              float* __restrict__ losses)
@@ -589,7 +648,22 @@ hipError_t launch_mc_loss(const float* x, float* losses, int W, int64_t ld, cons
 {
     const int64_t nb = mc_entries(b);
     const int nblk = (int)((nb + kMcEntriesPerBlock - 1) / kMcEntriesPerBlock);
-    if (nblk > 0) {
+    const bool vec = b.r % 4 == 0 && b.r <= 256 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && ld % 4 == 0;
+    if (nblk > 0 && vec) {
+        dim3 grid((unsigned)nblk, (unsigned)W);
+#define LSGD_MC_LAUNCH(LPE)                                                                                      \
+    hipLaunchKernelGGL((mc_loss_vec_kernel<LPE>), grid, dim3(kMcThreads), 0, s, x, ld, b.m, b.n, b.r, b.rows,   \
+                       b.cols, b.vals, b.batch_idx, nb, st.partials, nblk, b.entries)
+        const int r4 = b.r / 4;
+        if (r4 <= 1) LSGD_MC_LAUNCH(1);
+        else if (r4 <= 2) LSGD_MC_LAUNCH(2);
+        else if (r4 <= 4) LSGD_MC_LAUNCH(4);
+        else if (r4 <= 8) LSGD_MC_LAUNCH(8);
+        else if (r4 <= 16) LSGD_MC_LAUNCH(16);
+        else if (r4 <= 32) LSGD_MC_LAUNCH(32);
+        else LSGD_MC_LAUNCH(64);
+#undef LSGD_MC_LAUNCH
+    } else if (nblk > 0) {
         dim3 grid((unsigned)nblk, (unsigned)W);
 #define LSGD_MC_LAUNCH(S)                                                                                              \
     hipLaunchKernelGGL((mc_grad_atomic_kernel<S, false>), grid, dim3(kMcThreads), 0, s, x, (float*)nullptr, ld, b.m, b.n, \

@@ -152,31 +152,20 @@ __device__ __forceinline__ void fused_store4(const FusedRow& r, FusedBatch<R>& b
 constexpr int kBK = 64;          // contraction tile
 constexpr int kLdk = kBK + 8;    // padded LDS row (bf16 elements): 144 B
 
-// 16-byte chunk position inside an LDS row.  Rows of a transposed-staged tile
-// are rotated by (row / 16): constant over the 16 consecutive rows that one
-// pass of a 16-byte fragment read touches (those stay conflict-free thanks to
-// the odd row stride), and different for the eight row groups whose 8-byte
-// transposing writes share a pass, which spreads them over all banks.
-template <bool SWZ> __device__ __forceinline__ int lds_chunk(int row, int chunk)
-{
-    return SWZ ? ((chunk + (row >> 4)) & 7) : chunk;
-}
+// An operand given as [k][n] (n contiguous: the weights in the d-input product, the activations in the
+// d-weight product) is staged in LDS as it lies in memory, 64 k-rows of BN + kPadN elements: the padding shifts
+// consecutive rows by 64 bytes, i.e. a quarter of the banks, so that the four rows one transposing read touches
+// cover all banks once.  The matrix cores want, per lane, eight consecutive k of one column n; the LDS
+// transposing read delivers that: in every group of 16 lanes, lane i supplies the address of four consecutive
+// elements, the 16 x 4 elements are taken as a 4 x 16 matrix (lanes 4r .. 4r+3 hold row r), and lane i receives
+// column i.  With lanes 4r .. 4r+3 pointing at k-row r, columns n0 .. n0+15, lane i gets (k0 .. k0+3, n0 + i).
+constexpr int kPadN = 32;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// Thread -> (n-group, k-group) of the transposing stage.  With four k-rows per
-// thread the sixteen lanes of a write pass hold both k-halves of a 16-byte
-// chunk and eight n-groups that are two apart.
-template <int BN, int THREADS> __device__ __forceinline__ void trans_map(int tid, int& ng, int& kg)
+__device__ __forceinline__ s16x4 lds_read_tr(const uint16_t* p)
 {
-    if (BN == 128 && THREADS == 256) {
-        kg = (tid & 1) | ((tid >> 5) << 1);
-        ng = (((tid >> 1) & 7) << 1) | ((tid >> 4) & 1);
-    } else if (BN == 256 && THREADS == 512) {
-        kg = (tid & 1) | ((tid >> 6) << 1);
-        ng = (((tid >> 1) & 7) << 1) | ((tid >> 4) & 1) | (((tid >> 5) & 1) << 4);
-    } else {
-        ng = tid % (BN / 8);
-        kg = tid / (BN / 8);
-    }
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
 }
 
 // BM x BN output tile per workgroup, WVM x WVN wavefronts, each owning (BM/WVM) x (BN/WVN).
@@ -190,12 +179,13 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
     constexpr int TM = WTM / 32, TN = WTN / 32;      // 32x32 MFMA tiles per wavefront
     constexpr int A_CHUNKS = BM * (kBK / 8) / kGemmThreads; // 16-byte chunks per thread
     constexpr int B_CHUNKS = BN * (kBK / 8) / kGemmThreads;
-    constexpr int KK = kBK * BN / 8 / kGemmThreads;  // k-rows per thread in the transposing stage
+    constexpr int LDN = BN + kPadN;                  // row of a [k][n]-staged tile
+    constexpr int B_TILE = TRANS_B ? kBK * LDN : BN * kLdk;   // elements of one B buffer
     constexpr int STAGES = (TM * TN > 4) ? 1 : 2;    // register stages of global prefetch (one beside 128 accumulator registers)
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
     uint16_t* As = smem;                              // [2][BM][kLdk]
-    uint16_t* Bs = smem + 2 * BM * kLdk;              // [2][BN][kLdk]
+    uint16_t* Bs = smem + 2 * BM * kLdk;              // [2][BN][kLdk], or [2][kBK][LDN] for a [k][n] operand
 
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int wm = wid / WVN, wn = wid % WVN;
@@ -235,7 +225,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // two register stages: the loads of k-steps kt+1 and kt+2 are in flight while kt is multiplied
-    constexpr int RB = TRANS_B ? KK : B_CHUNKS;
+    constexpr int RB = B_CHUNKS;
     u32x4 ra0[A_CHUNKS], ra1[STAGES == 2 ? A_CHUNKS : 1];
     u32x4 rb0[RB], rb1[STAGES == 2 ? RB : 1];
 
@@ -247,11 +237,11 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
             ra[c] = *reinterpret_cast<const u32x4*>(A + (int64_t)row * g.lda + k0 + ch * 8);
         }
         if (TRANS_B) {
-            int ng, kg;
-            trans_map<BN, kGemmThreads>(tid, ng, kg);
 #pragma unroll
-            for (int q = 0; q < KK; ++q)
-                rb[q] = *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + kg * KK + q) * g.ldb + n0 + ng * 8);
+            for (int c = 0; c < B_CHUNKS; ++c) {
+                const int id = tid + c * kGemmThreads, row = id / (BN / 8), ch = id % (BN / 8);
+                rb[c] = *reinterpret_cast<const u32x4*>(B + (int64_t)(k0 + row) * g.ldb + n0 + ch * 8);
+            }
         } else {
 #pragma unroll
             for (int c = 0; c < B_CHUNKS; ++c) {
@@ -262,30 +252,17 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
     };
     auto store_lds = [&](int buf, const u32x4* ra, const u32x4* rb) {
         uint16_t* as = As + buf * BM * kLdk;
-        uint16_t* bs = Bs + buf * BN * kLdk;
+        uint16_t* bs = Bs + buf * B_TILE;
 #pragma unroll
         for (int c = 0; c < A_CHUNKS; ++c) {
             const int id = tid + c * kGemmThreads, row = id >> 3, ch = id & 7;
             *reinterpret_cast<u32x4*>(as + row * kLdk + ch * 8) = ra[c];
         }
         if (TRANS_B) {
-            int ng, kg;
-            trans_map<BN, kGemmThreads>(tid, ng, kg);
-            const int kk0 = kg * KK;               // first k of this thread's micro-tile
 #pragma unroll
-            for (int n = 0; n < 8; ++n) {
-                // element (q, n) of the micro-tile is the (n&1) half of dword n/2 of rb[q]
-                uint32_t v[KK];
-#pragma unroll
-                for (int q = 0; q < KK; ++q) v[q] = (n & 1) ? (rb[q][n >> 1] >> 16) : (rb[q][n >> 1] & 0xFFFFu);
-                const int row = ng * 8 + n;
-                uint16_t* dst = bs + row * kLdk + lds_chunk<true>(row, kk0 >> 3) * 8 + (kk0 & 7);
-                if (KK == 4) {
-                    u32x2 o = {v[0] | (v[1] << 16), v[2] | (v[3] << 16)};
-                    *reinterpret_cast<u32x2*>(dst) = o;
-                } else {
-                    *reinterpret_cast<uint32_t*>(dst) = v[0] | (v[1] << 16);
-                }
+            for (int c = 0; c < B_CHUNKS; ++c) {
+                const int id = tid + c * kGemmThreads, row = id / (BN / 8), ch = id % (BN / 8);
+                *reinterpret_cast<u32x4*>(bs + row * LDN + ch * 8) = rb[c];
             }
         } else {
 #pragma unroll
@@ -298,7 +275,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
 
     auto compute = [&](int buf) {
         const uint16_t* as = As + buf * BM * kLdk;
-        const uint16_t* bs = Bs + buf * BN * kLdk;
+        const uint16_t* bs = Bs + buf * B_TILE;
 #pragma unroll
         for (int kk = 0; kk < kBK / 16; ++kk) {
             bf16x8 af[TM], bfr[TN];
@@ -310,8 +287,19 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const int row = wn * WTN + j * 32 + (lane & 31);
-                bfr[j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + lds_chunk<TRANS_B>(row, ch) * 8);
+                if (TRANS_B) {
+                    // lane (n = lane % 32, k-half = lane / 32): k = 16 kk + 8 (lane / 32) + 0..7 of column n
+                    const int i = lane & 15;
+                    const int col = wn * WTN + j * 32 + (lane & 16) + 4 * (i & 3);
+                    const int row = kk * 16 + 8 * (lane >> 5) + (i >> 2);
+                    const s16x4 lo = lds_read_tr(bs + row * LDN + col);
+                    const s16x4 hi = lds_read_tr(bs + (row + 4) * LDN + col);
+                    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    bfr[j] = __builtin_bit_cast(bf16x8, v);
+                } else {
+                    const int row = wn * WTN + j * 32 + (lane & 31);
+                    bfr[j] = *reinterpret_cast<const bf16x8*>(bs + row * kLdk + ch * 8);
+                }
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -419,46 +407,83 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
         }
         return;
     }
+    if (EPI == EPI_FWD || EPI == EPI_DX) {
+        // bf16 results leave through LDS (the operand buffers are free now): lanes hold single columns, a
+        // row-major tile in LDS turns them into 16-byte pieces of rows, 256 contiguous bytes per 16 lanes.
+        constexpr int LDT = BN + kPadN;                   // rows shift by 64 bytes, as for the transposing read
+        constexpr int T_CHUNKS = BM * (BN / 8) / kGemmThreads;
+        static_assert((size_t)BM * LDT <= (size_t)2 * (BM * kLdk + B_TILE), "result tile fits the operand buffers");
+        uint16_t* T = smem;
+        uint16_t* out = g.out + (int64_t)w * g.sOut;
+        if (EPI == EPI_DX) {
+            // the ReLU mask (h_{k-1} != 0) arrives as 16-byte pieces too and is read back per lane with the
+            // transposing read: rows R .. R+3 of the lane's own column, the layout of four accumulators
+            const uint16_t* mask = g.mask + (int64_t)w * g.sMask;
+            u32x4 mk[T_CHUNKS];
+#pragma unroll
+            for (int c = 0; c < T_CHUNKS; ++c) {
+                const int id = tid + c * kGemmThreads, row = id / (BN / 8), ch = id % (BN / 8);
+                mk[c] = *reinterpret_cast<const u32x4*>(mask + (int64_t)(m0 + row) * g.ldmask + n0 + ch * 8);
+            }
+#pragma unroll
+            for (int c = 0; c < T_CHUNKS; ++c) {
+                const int id = tid + c * kGemmThreads, row = id / (BN / 8), ch = id % (BN / 8);
+                *reinterpret_cast<u32x4*>(T + row * LDT + ch * 8) = mk[c];
+            }
+            __syncthreads();
+        }
+        uint16_t* outT = (EPI == EPI_DX) ? g.outT + (int64_t)w * g.sOutT : nullptr;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int nl = wn * WTN + j * 32 + (lane & 31);               // column inside the tile
+                const int rb = wm * WTM + i * 32 + (lane >> 5) * 4;            // first row inside the tile
+                if (EPI == EPI_FWD) {
+                    const float b = g.bias[(int64_t)w * g.sBias + n0 + nl];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float z = acc[i][j][v] + b;
+                        T[(rb + 8 * (v >> 2) + (v & 3)) * LDT + nl] = f32_to_bf16_rne(z > 0.f ? z : 0.f);
+                    }
+                } else {
+                    const int l16 = lane & 15;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        // every 4 x 16 block of the tile is read and then overwritten by the same 16 lanes
+                        const s16x4 on = lds_read_tr(T + (rb + 8 * q + (l16 >> 2)) * LDT + wn * WTN + j * 32 + (lane & 16) + 4 * (l16 & 3));
+                        uint32_t pk[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const uint16_t d = on[r] != 0 ? f32_to_bf16_rne(acc[i][j][q * 4 + r]) : (uint16_t)0;
+                            T[(rb + 8 * q + r) * LDT + nl] = d;
+                            pk[r] = d;
+                        }
+                        // the transposed copy: the lane's four rows are 8 contiguous bytes of it
+                        const u32x2 o = {pk[0] | (pk[1] << 16), pk[2] | (pk[3] << 16)};
+                        *reinterpret_cast<u32x2*>(outT + (int64_t)(n0 + nl) * g.ldoutT + m0 + rb + 8 * q) = o;
+                    }
+                }
+            }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < T_CHUNKS; ++c) {
+            const int id = tid + c * kGemmThreads, row = id / (BN / 8), ch = id % (BN / 8);
+            *reinterpret_cast<u32x4*>(out + (int64_t)(m0 + row) * g.ldout + n0 + ch * 8) = *reinterpret_cast<const u32x4*>(T + row * LDT + ch * 8);
+        }
+        return;
+    }
+    float* C = g.C + (int64_t)w * g.sC;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int n = n0 + wn * WTN + j * 32 + (lane & 31);
             const int mb = m0 + wm * WTM + i * 32 + (lane >> 5) * 4;
-            if (EPI == EPI_FWD) {
-                const float b = g.bias[(int64_t)w * g.sBias + n];
-                uint16_t* out = g.out + (int64_t)w * g.sOut;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = mb + 8 * (v >> 2) + (v & 3);
-                    float z = acc[i][j][v] + b;
-                    out[(int64_t)m * g.ldout + n] = f32_to_bf16_rne(z > 0.f ? z : 0.f);
-                }
-            } else if (EPI == EPI_DX) {
-                const uint16_t* mask = g.mask + (int64_t)w * g.sMask;
-                uint16_t* out = g.out + (int64_t)w * g.sOut;
-                uint16_t* outT = g.outT + (int64_t)w * g.sOutT;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint32_t pk[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int m = mb + 8 * q + r;
-                        const bool on = mask[(int64_t)m * g.ldmask + n] != 0;
-                        const uint16_t d = on ? f32_to_bf16_rne(acc[i][j][q * 4 + r]) : (uint16_t)0;
-                        out[(int64_t)m * g.ldout + n] = d;
-                        pk[r] = d;
-                    }
-                    u32x2 o = {pk[0] | (pk[1] << 16), pk[2] | (pk[3] << 16)};
-                    *reinterpret_cast<u32x2*>(outT + (int64_t)n * g.ldoutT + mb + 8 * q) = o;
-                }
-            } else {
-                float* C = g.C + (int64_t)w * g.sC;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int m = mb + 8 * (v >> 2) + (v & 3);
-                    C[(int64_t)m * g.ldc + n] = acc[i][j][v];
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int m = mb + 8 * (v >> 2) + (v & 3);
+                C[(int64_t)m * g.ldc + n] = acc[i][j][v];
             }
         }
 }
@@ -466,7 +491,7 @@ __global__ __launch_bounds__(64 * WVM * WVN, (WVM * WVN > 4) ? 1 : 2) void gemm_
 template <int BM, int BN, int WVM, int WVN, bool TRANS_B, int EPI>
 static void launch_gemm(const GemmArgs& g, int W, hipStream_t s)
 {
-    const size_t lds = (size_t)2 * (BM + BN) * kLdk * sizeof(uint16_t);
+    const size_t lds = (size_t)2 * (BM * kLdk + (TRANS_B ? kBK * (BN + kPadN) : BN * kLdk)) * sizeof(uint16_t);
     static bool configured = false;
     if (!configured) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, WVM, WVN, TRANS_B, EPI>),
@@ -489,6 +514,11 @@ static bool try_mfma(const GemmArgs& g, int W, hipStream_t s)
 {
     if (g.K % kBK || g.M % 128 || g.N % 64 || !aligned_for_mfma(g)) return false;
     if (EPI == EPI_DX && (g.ldoutT % 4 || (reinterpret_cast<uintptr_t>(g.outT) & 7u) || g.sOutT % 4)) return false;
+    if (EPI == EPI_FWD || EPI == EPI_DX) {                 // 16-byte pieces of the result rows (and of the mask rows)
+        auto a16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+        if (!a16(g.out) || g.ldout % 8 || g.sOut % 8) return false;
+        if (EPI == EPI_DX && (!a16(g.mask) || g.ldmask % 8 || g.sMask % 8)) return false;
+    }
     if (EPI == EPI_DWU) {                                  // float4 rows of x, m, Z; 8-byte groups of the bf16 copy
         auto a16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
         if (g.colC % 4 || g.ldc % 4 || g.sC % 4 || !a16(g.fu.x) || !a16(g.fu.m) || !a16(g.fu.Z) ||
