@@ -15,15 +15,14 @@
 // the narrow classifier layer.
 //
 // Operand layouts for the MFMA kernel.  A lane feeds the matrix core eight
-// consecutive values along the contraction index, so each operand must be
-// contiguous along that index in LDS:
+// consecutive values along the contraction index:
 //   forward : A = h_{k-1} [B][d_in]   B-operand = W_k [d_out][d_in]    both contiguous in d_in
 //   d-input : A = delta_k [B][d_out]  B-operand = W_k [d_out][d_in]    contraction over d_out: rows of W
 //   d-weight: A = delta_k^T [d_out][B] B-operand = h_{k-1} [B][d_in]   contraction over B: rows of h
-// In the last two the B-operand is contiguous along the *output* column, so
-// its tile is transposed on the way from global memory into LDS (a 4x8 or 2x8
-// register micro-transpose per thread).  delta_k is stored in both layouts by
-// the kernel that produces it.
+// In the last two the B-operand is contiguous along the *output* column.  Its
+// tile is staged in LDS as it lies in memory and the fragments are fetched
+// with the LDS transposing read (see lds_read_tr).  delta_k is stored in both
+// layouts by the kernel that produces it.
 #include "common.h"
 #include "update_math.h"
 
