@@ -710,32 +710,45 @@ __global__ __launch_bounds__(256) void fwd_narrow_kernel(const uint16_t* __restr
     }
 }
 
-// db[o] = sum_b deltaT[o][b] with 16-byte loads, half a wavefront per o.  B % 8 == 0, rows 16-byte aligned.
-__global__ __launch_bounds__(256) void db_vec_kernel(const uint16_t* __restrict__ deltaT, int64_t sD, int B, int dout, float* __restrict__ g,
-                                                     int64_t sG, FusedUpdate fu, int64_t col0)
+// Bias gradients of all layers in one launch: db_k[o] = sum_b deltaT_k[o][b] with 16-byte loads, half a
+// wavefront per output, eight outputs per workgroup.  B % 8 == 0, rows 16-byte aligned.
+struct BiasLayers {
+    int n;                    // layers
+    int first_block[65];      // workgroups of layer i: first_block[i] .. first_block[i+1]
+    int dout[64];
+    int64_t dT[64];           // delta^T of the layer, element offset in a worker's scratch
+    int64_t col[64];          // column of the layer's bias in the parameter row
+};
+
+__global__ __launch_bounds__(256) void db_all_kernel(const uint16_t* __restrict__ scratch, int64_t sD, int B, BiasLayers t,
+                                                     float* __restrict__ g, int64_t sG, FusedUpdate fu)
 {
+    int layer = 0;
+    while (layer + 1 < t.n && (int)blockIdx.x >= t.first_block[layer + 1]) ++layer;   // uniform
     const int lane = threadIdx.x & 63, l = lane & 31;
-    const int o = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 2 + (lane >> 5);
+    const int o = (((int)blockIdx.x - t.first_block[layer]) * 4 + (threadIdx.x >> 6)) * 2 + (lane >> 5);
     const int w = blockIdx.y;
+    const int dout = t.dout[layer];
     float acc = 0.f;
     if (o < dout) {
-        const u32x4* dt = reinterpret_cast<const u32x4*>(deltaT + (int64_t)w * sD + (int64_t)o * B);
+        const u32x4* dt = reinterpret_cast<const u32x4*>(scratch + (int64_t)w * sD + t.dT[layer] + (int64_t)o * B);
         for (int c = l; c < B / 8; c += 32) {
             float a[8];
             unpack8(dt[c], a);
 #pragma unroll
-            for (int t = 0; t < 8; ++t) acc += a[t];
+            for (int q = 0; q < 8; ++q) acc += a[q];
         }
     }
 #pragma unroll
     for (int d = 1; d < 32; d <<= 1) acc += __shfl_xor(acc, d, 64);
     if (l == 0 && o < dout) {
+        const int64_t col = t.col[layer] + o;
         if (fu.enabled) {
             const int off[1] = {0};
             const float gv[1] = {acc};
-            fused_apply<1>(fused_row(fu, w, sG), col0 + o, off, gv);
+            fused_apply<1>(fused_row(fu, w, sG), col, off, gv);
         } else {
-            g[(int64_t)w * sG + o] = acc;
+            g[(int64_t)w * sG + col] = acc;
         }
     }
 }
@@ -1036,15 +1049,27 @@ hipError_t launch_mlp_backward(const uint16_t* xb, const float* x, float* g, int
                                    dout, g + woff[k], ld, fu, woff[k]);
             }
         }
-        // db_k
-        {
-            const uint16_t* dTk = sc16 + p.dT[k];
-            if (B % 8 == 0 && sW16 % 8 == 0 && (reinterpret_cast<uintptr_t>(dTk) & 15u) == 0)
-                hipLaunchKernelGGL(db_vec_kernel, dim3((unsigned)((dout + 7) / 8), (unsigned)W), dim3(256), 0, s, dTk, sW16, B, dout,
-                                   g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
-            else
-                hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, dTk, sW16, B, dout,
-                                   g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
+    }
+    // db_k of every layer (delta^T_k is complete once layer k+1 has been processed; the biases' columns
+    // are nobody else's): one launch when the rows allow 16-byte loads, else one per layer
+    if (B % 8 == 0 && sW16 % 8 == 0 && (reinterpret_cast<uintptr_t>(sc16) & 15u) == 0) {
+        BiasLayers t{};
+        t.n = L;
+        int blocks = 0;
+        for (int k = 1; k <= L; ++k) {
+            t.first_block[k - 1] = blocks;
+            t.dout[k - 1] = b.dims[k];
+            t.dT[k - 1] = p.dT[k];
+            t.col[k - 1] = woff[k] + (int64_t)b.dims[k] * b.dims[k - 1];
+            blocks += (b.dims[k] + 7) / 8;
+        }
+        t.first_block[L] = blocks;
+        hipLaunchKernelGGL(db_all_kernel, dim3((unsigned)blocks, (unsigned)W), dim3(256), 0, s, sc16, sW16, B, t, g, ld, fu);
+    } else {
+        for (int k = L; k >= 1; --k) {
+            const int din = b.dims[k - 1], dout = b.dims[k];
+            hipLaunchKernelGGL(db_kernel, dim3((unsigned)((dout + 3) / 4), (unsigned)W), dim3(256), 0, s, sc16 + p.dT[k], sW16, B, dout,
+                               g + woff[k] + (int64_t)dout * din, ld, fu, woff[k] + (int64_t)dout * din);
         }
     }
     if (fused) return hipGetLastError();          // g is not written, so there is no padding to clear
