@@ -148,3 +148,10 @@ def test_full_size_matrix_completion_config_two_steps():
         if t == 0:
             assert rel_l2_rows(pr.g.cpu().numpy()[:, :prob.P], g_ora[:, :prob.P]).max() < 1e-5
         pr.check_state(1e-4, f"step {t}")
+    # objective-only evaluation at the parameters after the two steps (what re-selecting after a step costs):
+    # the oracle's losses at its own state, which agrees with the GPU's to 1e-4
+    pr.ora.grad_loss_mc(prob.m, prob.n, prob.r, prob.rows, prob.cols, prob.vals, idx[0], c)
+    g_before = pr.g.clone()
+    pr.pop.loss(b0)
+    np.testing.assert_allclose(pr.pop.get_losses(), pr.ora.losses, rtol=2e-4)
+    assert torch.equal(pr.g, g_before)
