@@ -126,9 +126,12 @@ typedef struct {
 typedef struct {
     int32_t n_layers;    /* number of weight matrices                              */
     const int32_t* dims; /* host [n_layers+1]: d0 (input) ... d_L (classes)        */
-    const uint16_t* X;   /* device [W, B, d0] bf16 bit patterns                    */
+    const void* X;       /* device [W, B, d0]: bf16 bit patterns (uint16), or fp32
+                            values when x_is_fp32 (rounded to bf16, to nearest even,
+                            on the way in: a copy in the workspace)                */
     const int32_t* y;    /* device [W, B] class labels in [0, d_L)                 */
     int32_t B;           /* samples per worker                                     */
+    int32_t x_is_fp32;   /* 0: X holds bf16 bit patterns; 1: X holds fp32 values   */
 } lsgd_mlp_batch;
 
 typedef struct {

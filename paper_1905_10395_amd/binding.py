@@ -48,7 +48,7 @@ class _MC(C.Structure):
 
 class _MLP(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("dims", C.POINTER(C.c_int32)), ("X", C.c_void_p), ("y", C.c_void_p),
-                ("B", C.c_int32)]
+                ("B", C.c_int32), ("x_is_fp32", C.c_int32)]
 
 
 class _Batch(C.Structure):
@@ -139,12 +139,13 @@ class MCBatch:
 
 
 class MLPBatch:
-    """dims: [d0..dL]; X: bfloat16 (or int16/uint16 bit patterns) [W,B,d0]; y: int32 [W,B]."""
+    """dims: [d0..dL]; X: bfloat16 (or int16/uint16 bit patterns) or float32 [W,B,d0]; y: int32 [W,B]."""
 
     def __init__(self, dims, X, y):
         self.keep = (X, y)
         self._dims = (C.c_int32 * len(dims))(*[int(d) for d in dims])
-        self._d = _MLP(len(dims) - 1, self._dims, X.data_ptr(), y.data_ptr(), int(y.shape[-1]))
+        self._d = _MLP(len(dims) - 1, self._dims, X.data_ptr(), y.data_ptr(), int(y.shape[-1]),
+                       1 if X.dtype == torch.float32 else 0)
         self.c = _Batch(BATCH_MLP, C.cast(C.pointer(self._d), C.c_void_p))
 
 

@@ -869,6 +869,15 @@ __global__ __launch_bounds__(512) void dx_narrow_kernel(const uint16_t* __restri
     }
 }
 
+// h_0 = bf16(X) for fp32 inputs: n values per worker, rounded to nearest even
+__global__ __launch_bounds__(256) void cast_input_kernel(const float* __restrict__ X, int64_t n, uint16_t* __restrict__ out, int64_t sOut)
+{
+    const int w = blockIdx.y;
+    const float* src = X + (int64_t)w * n;
+    uint16_t* dst = out + (int64_t)w * sOut;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = f32_to_bf16_rne(src[i]);
+}
+
 __global__ __launch_bounds__(256) void zero_pad_kernel(float* __restrict__ g, int64_t P, int64_t ld)
 {
     const int64_t c = P + (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -888,6 +897,7 @@ struct MlpPlan {
     int64_t d[64];      // delta[k], k = 1..L [B][d_k]
     int64_t dT[64];     // delta^T[k]         [d_k][B]
     int64_t logits;     // fp32 [B][C], offset in bytes from the worker's base
+    int64_t x0;         // bf16 copy of fp32 inputs [B][d_0] (only when the batch brings fp32 inputs)
     int64_t per_worker; // bytes per worker
 };
 
@@ -905,6 +915,7 @@ MlpPlan make_plan(const lsgd_mlp_batch& b, int W)
         p.dT[k] = o / 2; o = up16(o + n);
     }
     p.logits = o; o = up16(o + (int64_t)b.B * b.dims[p.L] * 4);
+    if (b.x_is_fp32) { p.x0 = o / 2; o = up16(o + (int64_t)b.B * b.dims[0] * 2); }
     p.per_worker = (o + 255) / 256 * 256;
     p.bytes = (std::size_t)p.per_worker * (std::size_t)W;
     return p;
@@ -943,10 +954,20 @@ hipError_t launch_mlp_forward(const uint16_t* xb, const float* x, float* losses,
     { int64_t o = 0; for (int k = 1; k <= L; ++k) { woff[k] = o; o += (int64_t)b.dims[k] * b.dims[k - 1] + b.dims[k]; } }
 
     // ---- forward ----
+    const uint16_t* X0 = static_cast<const uint16_t*>(b.X);
+    int64_t sX0 = (int64_t)B * b.dims[0];
+    if (b.x_is_fp32) {                                     // the bf16 copy both passes read
+        const int64_t n = (int64_t)B * b.dims[0];
+        int64_t blocks = (n + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(cast_input_kernel, dim3((unsigned)blocks, (unsigned)W), dim3(256), 0, s, static_cast<const float*>(b.X), n,
+                           sc16 + p.x0, sW16);
+        X0 = sc16 + p.x0; sX0 = sW16;
+    }
     for (int k = 1; k <= L; ++k) {
         const int din = b.dims[k - 1], dout = b.dims[k];
-        const uint16_t* Hin = (k == 1) ? b.X : sc16 + p.h[k - 1];
-        const int64_t sHin = (k == 1) ? (int64_t)B * din : sW16;
+        const uint16_t* Hin = (k == 1) ? X0 : sc16 + p.h[k - 1];
+        const int64_t sHin = (k == 1) ? sX0 : sW16;
         const float* bias = x + woff[k] + (int64_t)dout * din;
         bool done = false;
         if (k < L) {
@@ -1002,10 +1023,13 @@ hipError_t launch_mlp_backward(const uint16_t* xb, const float* x, float* g, int
     int64_t woff[64];
     { int64_t o = 0; for (int k = 1; k <= L; ++k) { woff[k] = o; o += (int64_t)b.dims[k] * b.dims[k - 1] + b.dims[k]; } }
 
+    // fp32 inputs: the forward pass of this step left their bf16 copy in the scratch
+    const uint16_t* X0 = b.x_is_fp32 ? sc16 + p.x0 : static_cast<const uint16_t*>(b.X);
+    const int64_t sX0 = b.x_is_fp32 ? sW16 : (int64_t)B * b.dims[0];
     for (int k = L; k >= 1; --k) {
         const int din = b.dims[k - 1], dout = b.dims[k];
-        const uint16_t* Hin = (k == 1) ? b.X : sc16 + p.h[k - 1];
-        const int64_t sHin = (k == 1) ? (int64_t)B * din : sW16;
+        const uint16_t* Hin = (k == 1) ? X0 : sc16 + p.h[k - 1];
+        const int64_t sHin = (k == 1) ? sX0 : sW16;
         // delta_{k-1}
         if (k > 1) {
             GemmArgs a{};

@@ -91,6 +91,41 @@ def test_mlp_grad_loss_matches_oracle(dims, W, B):
     assert np.all(g[:, P:] == 0)
 
 
+@pytest.mark.parametrize("dims,W,B", [([12, 16, 5], 2, 9), ([192, 256, 128, 10], 3, 128)])
+def test_mlp_fp32_inputs_are_rounded_to_bf16_on_load(dims, W, B):
+    """X given as fp32: h_0 = bf16(X), to nearest even, is the first rounding point of the forward pass.  The oracle
+    gets the bits torch's CPU conversion produces; the GPU gets the fp32 values and must behave exactly as when it
+    is handed those bits."""
+    P = wl.mlp_param_count(dims)
+    ld = wl.padded_ld(P)
+    x0 = wl.mlp_init(W, dims, ld=ld, seed=77)
+    Xb, y = wl.gmm_batch(W, B, wl.gmm_means(dims[0], dims[-1], seed=77), 0, seed=77)
+    r = wl.stream("mlp_fp32_inputs", W, B)
+    X32 = (Xb.view(np.uint16).astype(np.uint32) << 16).view(np.float32) * (1.0 + 3e-3 * r.standard_normal(Xb.shape, dtype=np.float32))
+    bits = torch.from_numpy(X32).to(torch.bfloat16).view(torch.int16).numpy()
+    assert (bits != Xb.view(np.int16)).any()                  # the perturbation crosses rounding boundaries
+    b32 = L.MLPBatch(dims, dev(X32), dev(y))
+    b16 = L.MLPBatch(dims, dev(bits).view(torch.bfloat16), dev(y))
+    pr = Pair(x0, wl.equal_group_offsets(W, 1), P=P, shadow=True, largest_batch=b32)
+    pr.ora.grad_loss_mlp(dims, bits.view(Xb.dtype), y)
+    pr.pop.grad_loss(b32)
+    torch.cuda.synchronize()
+    g32 = pr.g.clone()
+    l32 = pr.pop.get_losses()
+    np.testing.assert_allclose(l32, pr.ora.losses, rtol=1e-4)
+    check_grads(g32.cpu().numpy()[:, :P], pr.ora.g[:, :P], dims)
+    pr.pop.grad_loss(b16)
+    torch.cuda.synchronize()
+    assert torch.equal(pr.g, g32) and pr.pop.get_losses() == l32
+    # the bf16 copy lives in the workspace: a population sized for bf16 batches says so instead of overrunning it
+    if L.workspace_bytes(W, P, ld, 1, batch=b32) > L.workspace_bytes(W, P, ld, 1, batch=b16):
+        small = Pair(x0, wl.equal_group_offsets(W, 1), P=P, shadow=True, largest_batch=b16)
+        with pytest.raises(L.LsgdError, match="workspace"):
+            small.pop.grad_loss(b32)
+    else:
+        assert B * dims[0] * 2 < 256                          # only a copy that fits the rounding slack is free
+
+
 def later_layer_wmax(x, dims):
     """largest |weight| of the layers that read a quantised activation (all but the first)"""
     off, w = dims[0] * dims[1] + dims[1], 0.0
