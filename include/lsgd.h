@@ -10,7 +10,7 @@
  *                           (Section 2: stochastic gradient g_t^{j,i}; Section
  *                           3.1.3: one loss sample per worker)
  *   2. lsgd_select_leaders  segmented argmin of the losses (Eq. 1 / Eq. 2;
- *                           Algorithm 1 "determine the local / global best")
+ *                           the leader-picking steps of Algorithm 1)
  *   3. lsgd_pull_update     x_i <- x_i - eta*(g_i + lam_L (x_i - z_local)
  *                                              + lam_G (x_i - z_global))
  *                           (supplement B.1; Eq. 3), optional momentum
@@ -218,8 +218,8 @@ lsgd_status lsgd_pull_update(lsgd_population* pop, float eta, float lambda_L, fl
 lsgd_status lsgd_step(lsgd_population* pop, const lsgd_batch* batch, float eta, float lambda_L,
                       float lambda_G, const uint8_t* refresh_local, int refresh_global);
 
-/* Communication pull of Algorithm 1 ("determine the local / global best
- * workers", "pull to the local / global best workers"): captures every leader
+/* Communication pull of Algorithm 1 (its two blocks that pick the best
+ * workers and move everyone towards them): captures every leader
  * re-selected since the last update (copied from x before any row changes, and
  * written to z_snapshot when it exists, also when its coefficient is 0), then
  *   groups whose local leader was re-selected:  x <- x - lambda_L (x - z_local)
@@ -243,8 +243,8 @@ enum {
  *   then, when comm has LSGD_COMM_LOCAL / LSGD_COMM_GLOBAL: select_leaders from
  *   this iteration's losses (comm_local_mask: host [n_groups] choosing the
  *   groups that communicate, NULL = all) followed by lsgd_leader_pull.
- * Before the first iteration the caller initialises the leaders (Algorithm 1,
- * "Initialize"): grad_loss, select_leaders(all), lsgd_leader_pull(0, 0).
+ * Before the first iteration the caller initialises the leaders (the
+ * initialisation block of Algorithm 1): grad_loss, select_leaders(all), lsgd_leader_pull(0, 0).
  * Needs z_snapshot.  eta must be non-zero when a gamma is.                      */
 lsgd_status lsgd_step_alg1(lsgd_population* pop, const lsgd_batch* batch, float eta, float gamma_L,
                            float gamma_G, float lambda_L, float lambda_G, int comm,

@@ -12,7 +12,8 @@
  *     fp64 and rounded once to fp32 where it is stored.
  *   - Workers are rows of x[W, ld]; group j owns rows [off[j], off[j+1]).
  *   - Z[(G+1), ld] holds the leader copies kept between communications
- *     (Algorithm 1 "Set x~^j, x~"; supplement B.1, communication periods):
+ *     (Algorithm 1, the leader variables set at initialisation and at each
+ *     communication; supplement B.1, communication periods):
  *     rows 0..G-1 local leaders, row G the global leader.
  *
  * Pins (tests/test_oracle_*.py): zero pull coefficients reduce to SGD; the
@@ -49,9 +50,9 @@
 #define ORACLE_MOMENTUM_GRAD_ONLY  8
 
 /* ------------------------------------------------------------------ */
-/* Leader selection: Eq. 1/2 argmin definitions; Algorithm 1 "Determine
- * the local best workers / the global best worker".  Ties go to the lowest
- * index; NaN counts as +infinity.                                      */
+/* Leader selection: Eq. 1/2 argmin definitions; the steps of Algorithm 1
+ * that pick the best worker of each group and of all groups.  Ties go to
+ * the lowest index; NaN counts as +infinity.                            */
 /* ------------------------------------------------------------------ */
 static double sel_value(float v) { return isnan(v) ? INFINITY : (double)v; }
 

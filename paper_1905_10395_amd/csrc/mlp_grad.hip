@@ -1,7 +1,7 @@
 // Per-worker gradient and loss of a fully connected ReLU classifier with softmax
 // cross-entropy, for all W workers of the population at once (each worker has
-// its own weights).  This is the "stochastic gradient g_t^{j,i} on the
-// worker's own minibatch" of arXiv 1905.10395 (Section 2) for the MLP
+// its own weights).  This is the stochastic gradient g_t^{j,i} that a worker
+// takes on its own minibatch in arXiv 1905.10395 (Section 2), for the MLP
 // workload: bf16 matrix operands, fp32 accumulation, fp32 gradients.
 //
 //   forward   z_k = h_{k-1} W_k^T + b_k ; h_k = bf16(relu(z_k)) ; logits fp32

@@ -1,6 +1,6 @@
 // Leader selection: segmented argmin of the workers' losses (Eq. 1 / Eq. 2 of
-// arXiv 1905.10395; Algorithm 1, "determine the local best workers" and "the
-// global best worker").  Ties resolve to the lowest worker index and NaN
+// arXiv 1905.10395; the steps of Algorithm 1 that pick the best worker of each
+// group and of all groups).  Ties resolve to the lowest worker index and NaN
 // counts as +infinity.
 //
 // A loss and its worker index are packed into one 64-bit key whose unsigned
